@@ -1,0 +1,206 @@
+/*
+ * liblookahead -- the lookahead-decoding verification step on one MI355X (gfx950).
+ *
+ * One step pushes a small block of candidate tokens (one real next-token row, W(N-1)
+ * lookahead-window rows, G(N-1) n-gram verification rows) through a Mistral-family layer
+ * stack against a growing KV cache, under an explicit per-row visibility mask, then
+ * unembeds every row, takes the greedy argmax and accepts the longest confirmed n-gram.
+ * Paper: "Privacy-Aware Split Inference with Speculative Decoding for LLMs over WANs",
+ * Section 3.1 (layer partition, model shapes), 3.3 (KV cache on the side that owns the
+ * layers; crop, relocation, custom masks), 4.1 (sequential step), 4.3 (lookahead decoding),
+ * 4.4 (explicit masks for multi-token steps), 6.5 (output identical to greedy decoding).
+ * The paper's local/cloud halves are layer ranges of one model here; its WAN transport is
+ * not part of this library.  The fields its frame header carries (Section 3.2: tensor
+ * shapes, cache crop position, mask) are arguments of la_forward_layers / la_ngram_accept.
+ *
+ * Conventions
+ *  - Every function returns LA_OK (0) or a negative la_status; none throws or exits.
+ *    la_last_error() gives the text of the calling thread's last failure.
+ *  - "device" pointers are HIP device memory owned by the caller and borrowed for the
+ *    call (the work is enqueued on `stream`; the memory must stay valid until the stream
+ *    has run it).  "host" pointers are ordinary process memory, read or written before the
+ *    call returns.  Handles (la_model, la_kv, la_pool) are owned by the library until freed.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work and do not synchronise unless stated.
+ *  - Matrices are row-major [in, out].  dtype LA_F32: weights and cache are float;
+ *    LA_BF16: weights and cache are bfloat16 bit patterns.  The residual stream (`hidden`),
+ *    norm gains, softmax and all accumulations are float in both cases.
+ *  - A block has Bp <= LA_MAX_ROWS rows.  Row b sits at cache row L+b while the block is
+ *    in flight, where L is the committed cache length kept on the device inside la_kv.
+ */
+#ifndef LA_H
+#define LA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LA_MAX_ROWS 64
+
+typedef enum {
+  LA_OK = 0,
+  LA_EINVAL = -1, /* bad shape, NULL pointer, Bp out of range, unsupported combination */
+  LA_ENOMEM = -2, /* device or host allocation failed */
+  LA_ERANGE = -3, /* the block would not fit: L + Bp > max_len, or layer out of range */
+  LA_EHIP = -4    /* a HIP call failed; la_last_error() has its text */
+} la_status;
+
+typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
+
+typedef struct la_model la_model; /* packed weights + per-model scratch */
+typedef struct la_kv la_kv;       /* K,V cache of all layers of one model + committed length */
+typedef struct la_pool la_pool;   /* n-gram pool */
+
+/* Model shape (Section 3.1 gives layer counts, hidden size, GQA head counts, vocabulary). */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_theta;
+  int32_t dtype; /* la_dtype */
+} la_model_desc;
+
+/* One layer's weights, device pointers, row-major [in, out], storage type = model dtype:
+ * wq [d, Hq*dh], wk, wv [d, Hkv*dh], wo [Hq*dh, d], wgate, wup [d, F], wdown [F, d];
+ * norm gains g_attn, g_mlp [d] are always float. */
+typedef struct {
+  const void *wq, *wk, *wv, *wo, *wgate, *wup, *wdown;
+  const float *g_attn, *g_mlp;
+} la_layer_weights;
+
+/* Lookahead parameters (Section 4.3; the paper's "n-gram size" is N): window width W,
+ * n-gram size N, at most G candidates verified per step.  Real rows per block:
+ * 1 + (W + G)(N - 1) <= LA_MAX_ROWS.  {W=0, N=1, G=0} is sequential decoding (Section 4.1). */
+typedef struct {
+  int32_t W, N, G;
+} la_lookahead_desc;
+
+/* Controller state, resident on the device between steps (the caller allocates
+ * sizeof(la_step_state) bytes of device memory; la_state_init fills it).
+ *   L        committed cache length = position of c0
+ *   c0       last committed token, row 0 of the next block
+ *   tok/pos/vis  the block to run next: token, position and visibility mask of each of the
+ *            Bp rows (bit j of vis[b]: row b attends to block row j; committed cache rows
+ *            are always visible)
+ *   win      lookahead window, win[r*W + c], r < N-1, c < W
+ *   cand     candidates being verified in this block, cand[k*(N-1) + j], k < n_cand
+ *   counters: steps, steps with at least one candidate token accepted, tokens emitted so
+ *            far, and for the last step: tokens emitted, winning candidate, match length. */
+typedef struct {
+  int32_t L, c0, n_cand, Bp;
+  int32_t steps, matched_steps, n_emitted, last_emitted, last_k, last_m;
+  int32_t error, reserved;
+  int32_t tok[LA_MAX_ROWS];
+  int32_t pos[LA_MAX_ROWS];
+  uint64_t vis[LA_MAX_ROWS];
+  int32_t win[LA_MAX_ROWS];
+  int32_t cand[LA_MAX_ROWS];
+} la_step_state;
+
+/* ---- model -------------------------------------------------------------------------- */
+
+/* Creates a model and packs its weights into the library's own layout (the caller may
+ * free its copies once `stream` has run).  `layers` is a host array of n_layers structs
+ * of device pointers, or NULL to add layers later with la_model_set_layer.  embed [V, d],
+ * unembed [d, V] (model dtype) and g_final [d] (float) are device pointers; each may be
+ * NULL if la_embed / la_unembed_argmax will not be called.
+ * LA_EINVAL: a dimension is not positive, Hq is not a multiple of Hkv, head_dim is odd,
+ * or (LA_BF16) d_model, Hq*dh, d_ffn are not multiples of 32, head_dim is not 64 or 128,
+ * or vocab is not a multiple of 16. */
+int la_init_model(const la_model_desc *desc, const la_layer_weights *layers, const void *embed,
+                  const float *g_final, const void *unembed, void *stream, la_model **out);
+int la_model_set_layer(la_model *m, int layer, const la_layer_weights *w, void *stream);
+void la_free_model(la_model *m);
+
+/* ---- KV cache (Section 3.3) ----------------------------------------------------------- */
+
+/* Cache for all layers of `m`: per layer K and V of max_len rows [Hkv, dh] in the model
+ * dtype, keys stored after RoPE.  max_len must leave room for the in-flight block:
+ * la_forward_layers needs L + Bp <= max_len.  The committed length L starts at 0. */
+int la_kv_alloc(const la_model *m, int max_len, la_kv **out);
+/* Sets L (the paper's cache crop: rows >= L are dead). */
+int la_kv_set_len(la_kv *kv, int L, void *stream);
+/* Reads L back; synchronises `stream`. */
+int la_kv_get_len(la_kv *kv, int *L_host, void *stream);
+/* Writes n rows [n, Hkv, dh] (device, model dtype, row-major) to rows row0.. of one layer. */
+int la_kv_fill(la_kv *kv, int layer, int row0, const void *k, const void *v, int n, void *stream);
+/* Reads n rows starting at row0 of one layer back into row-major [n, Hkv, dh] device buffers. */
+int la_kv_read(la_kv *kv, int layer, int row0, int n, void *k_out, void *v_out, void *stream);
+void la_free_kv(la_kv *kv);
+
+/* ---- the step ------------------------------------------------------------------------- */
+
+/* hidden[b, :] = embed[tok[b], :] for b < Bp (Section 4.1 step 1).  tok: device int32 [Bp],
+ * hidden: device float [Bp, d].  Token ids outside [0, vocab) are clamped. */
+int la_embed(la_model *m, const int32_t *tok, int Bp, float *hidden, void *stream);
+
+/* Runs the block through layers [layer_begin, layer_end) in place (Section 4.1 step 3 for
+ * one row; Sections 3.3 / 4.4 for a block): per layer RMSNorm, QKV projection, RoPE at
+ * pos[b], write of the block's K,V to cache rows L..L+Bp-1, grouped-query attention of row
+ * b over {cache rows < L} U {block rows j with bit j of vis[b]}, output projection +
+ * residual, RMSNorm, SwiGLU MLP + residual.
+ * hidden: device float [Bp, d], in/out.  pos: device int32 [Bp].  vis: device uint64 [Bp];
+ * every row must see at least itself.  Does not change L.
+ * LA_EINVAL: Bp not in 1..LA_MAX_ROWS or a NULL pointer; LA_ERANGE: layer range outside the
+ * model, or the host-side bound on L plus Bp exceeds max_len. */
+int la_forward_layers(la_model *m, int layer_begin, int layer_end, float *hidden, int Bp,
+                      const int32_t *pos, const uint64_t *vis, la_kv *kv, void *stream);
+
+/* ids[b] = argmax_v (rmsnorm(hidden[b]) * g_final) . unembed[:, v], ties to the lowest v
+ * (Section 4.1 step 5; Section 6.5: greedy argmax).  ids: device int32 [Bp].  top2: device
+ * float [Bp, 2] receiving the largest and second-largest logit of each row, or NULL. */
+int la_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
+                      void *stream);
+
+/* ---- n-gram pool and acceptance (Section 4.3) ----------------------------------------- */
+
+/* Pool keyed by token id: per key at most G distinct (N-1)-token continuations, refreshed
+ * on re-insert, least recently inserted evicted first, looked up most recent first. */
+int la_pool_alloc(int vocab, int N, int G, la_pool **out);
+void la_free_pool(la_pool *p);
+
+/* Starts a generation: clears the pool and (if seed_pool) inserts every N-gram of the prompt
+ * in order; sets the window to win[r][c] = prompt[(r + c) mod P], c0 = prompt[P-1], L = P-1,
+ * looks up the candidates of c0 and builds the first block of Bp rows into *state.  Also sets
+ * the cache length of `kv` to P-1 (the caller prefills rows 0..P-2 through
+ * la_forward_layers before or after this call).  prompt: device int32 [P], P >= 1. */
+int la_state_init(la_pool *p, la_kv *kv, const la_lookahead_desc *la, const int32_t *prompt, int P,
+                  int Bp, int seed_pool, la_step_state *state, void *stream);
+
+/* The accept phase of one step, all on the device: verifies the candidates against ids
+ * (the argmax of every block row), emits 1..N tokens (never more than max_total -
+ * state->n_emitted) to emitted[state->n_emitted..], moves the K,V rows of the accepted
+ * verification rows to cache rows L+1.. in every layer and advances L (the paper's cache
+ * relocation and crop), harvests W new n-grams into the pool, slides the window, looks up
+ * the candidates of the new c0 and builds the next block in *state.
+ * ids: device int32 [Bp]; emitted: device int32 [>= max_total]. */
+int la_ngram_accept(la_pool *p, la_kv *kv, const la_lookahead_desc *la, const int32_t *ids,
+                    la_step_state *state, int32_t *emitted, int max_total, void *stream);
+
+/* Host helper: positions and visibility masks of a lookahead block whose row 0 sits at
+ * position t with n_cand candidates present (no tokens involved).  pos_host [Bp],
+ * vis_host [Bp] are host arrays. */
+int la_lookahead_layout(const la_lookahead_desc *la, int t, int n_cand, int Bp, int32_t *pos_host,
+                        uint64_t *vis_host);
+
+/* ---- diagnostics ---------------------------------------------------------------------- */
+
+/* Per-kernel timing with HIP events on the launch stream.  While enabled every kernel
+ * launch is bracketed by events (this adds gaps: use it to attribute time, not to time a
+ * step).  la_profile_read synchronises, writes up to `cap` entries (kernel name, launches,
+ * total milliseconds) and returns the number of distinct kernels, then clears the record. */
+typedef struct {
+  char name[48];
+  int32_t launches;
+  float total_ms;
+} la_profile_entry;
+int la_profile_enable(int on);
+int la_profile_read(la_profile_entry *out_host, int cap);
+
+const char *la_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_H */
