@@ -309,7 +309,9 @@ extern "C" int la_kv_get_len(la_kv *kv, int *L_host, void *stream) {
 }
 
 static int kv_copy(la_kv *kv, int layer, int row0, void *k, void *v, int n, int to_cache, hipStream_t s) {
-  LA_REQUIRE(kv && k && v, LA_EINVAL, "NULL argument");
+  LA_REQUIRE(kv != nullptr, LA_EINVAL, "kv is NULL");
+  if (n == 0) return LA_OK;
+  LA_REQUIRE(k && v, LA_EINVAL, "NULL argument");
   LA_REQUIRE(layer >= 0 && layer < kv->n_layers, LA_ERANGE, "layer %d outside [0, %d)", layer, kv->n_layers);
   LA_REQUIRE(n >= 0 && row0 >= 0 && row0 + n <= kv->max_len, LA_ERANGE, "rows [%d, %d) outside the cache (max_len %d)",
              row0, row0 + n, kv->max_len);
