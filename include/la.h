@@ -196,6 +196,8 @@ typedef struct {
   float total_ms;
 } la_profile_entry;
 int la_profile_enable(int on);
+/* Restricts the bracketing to kernels of one name (NULL or "" = all kernels again). */
+int la_profile_select(const char *kernel_name);
 int la_profile_read(la_profile_entry *out_host, int cap);
 
 const char *la_last_error(void);

@@ -61,7 +61,7 @@ EXPORTS = [
     "la_init_model", "la_model_set_layer", "la_free_model", "la_kv_alloc", "la_kv_set_len", "la_kv_get_len",
     "la_kv_fill", "la_kv_read", "la_free_kv", "la_embed", "la_forward_layers", "la_unembed_argmax",
     "la_pool_alloc", "la_free_pool", "la_state_init", "la_ngram_accept", "la_lookahead_layout",
-    "la_profile_enable", "la_profile_read", "la_last_error",
+    "la_profile_enable", "la_profile_select", "la_profile_read", "la_last_error",
 ]
 
 
@@ -91,6 +91,7 @@ def _load():
         "la_ngram_accept": (i32, [vp, vp, C.POINTER(la_lookahead_desc), vp, vp, vp, i32, vp]),
         "la_lookahead_layout": (i32, [C.POINTER(la_lookahead_desc), i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
         "la_profile_enable": (i32, [i32]),
+        "la_profile_select": (i32, [C.c_char_p]),
         "la_profile_read": (i32, [C.POINTER(la_profile_entry), i32]),
         "la_last_error": (C.c_char_p, []),
     }
@@ -236,6 +237,10 @@ def la_lookahead_layout(W, N, G, t, n_cand, Bp):
 
 def la_profile_enable(on: bool):
     _check(lib.la_profile_enable(int(on)))
+
+
+def la_profile_select(name):
+    _check(lib.la_profile_select(name.encode() if name else None))
 
 
 def la_profile_read(cap=64):

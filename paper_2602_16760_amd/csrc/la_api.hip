@@ -34,10 +34,12 @@ struct ProfRec {
 static std::mutex g_prof_mu;
 static bool g_prof_on = false;
 static std::vector<ProfRec> g_prof;
+static char g_prof_only[48] = "";
 
 ProfScope::ProfScope(const char *name, hipStream_t s_) : s(s_), slot(-1) {
   if (!g_prof_on) return;
   std::lock_guard<std::mutex> lk(g_prof_mu);
+  if (g_prof_only[0] && strcmp(g_prof_only, name) != 0) return;
   ProfRec r{name, nullptr, nullptr};
   if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
   (void)hipEventRecord(r.a, s);
@@ -88,6 +90,14 @@ extern "C" const char *la_last_error(void) { return g_err; }
 extern "C" int la_profile_enable(int on) {
   std::lock_guard<std::mutex> lk(g_prof_mu);
   g_prof_on = on != 0;
+  return LA_OK;
+}
+
+extern "C" int la_profile_select(const char *name) {
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  g_prof_only[0] = 0;
+  if (name) strncpy(g_prof_only, name, sizeof(g_prof_only) - 1);
+  g_prof_only[sizeof(g_prof_only) - 1] = 0;
   return LA_OK;
 }
 

@@ -97,15 +97,18 @@ class Engine:
         torch.cuda.synchronize()
         return L
 
-    def start(self, prompt: np.ndarray, W: int, N: int, G: int, Bp: int, seed_pool: bool = True):
-        """Prefills prompt[:-1] and initialises the controller (pool, window, first block)."""
+    def start(self, prompt: np.ndarray, W: int, N: int, G: int, Bp: int, seed_pool: bool = True,
+              prefill: bool = True):
+        """Prefills prompt[:-1] (unless the cache rows are already there) and initialises the
+        controller (pool, window, first block)."""
         if self.pool is not None:
             B.la_free_pool(self.pool)
         self.la = (W, N, G)
         self.Bp = Bp
         self.pool = B.la_pool_alloc(self.shape.vocab, N, G)
         self.state = B.new_state()
-        self.prefill(np.asarray(prompt[:-1]))
+        if prefill:
+            self.prefill(np.asarray(prompt[:-1]))
         B.la_state_init(self.pool, self.kv, W, N, G, B.to_device(np.asarray(prompt, dtype=np.int32)), Bp,
                         seed_pool, self.state)
         torch.cuda.synchronize()
