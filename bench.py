@@ -145,7 +145,7 @@ def main():
     torch.cuda.synchronize()
     st0 = B.read_state(eng.state)
 
-    dominant = "gemm_gateup"
+    dominant = "layer_stack"   # the persistent kernel that runs all layers of the step
     B.la_profile_select(dominant)
     B.la_profile_enable(True)
     torch.cuda.synchronize()
@@ -174,7 +174,8 @@ def main():
     step_bytes = algorithmic_bytes(shape, n_layers, L_mid, BP)
     gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
     launches, total_ms = prof.get(dominant, (0, 0.0))
-    dom_bytes = 2 * 2 * shape.d_model * shape.d_ffn  # gate + up weights, bf16, read once per launch
+    # per launch: every layer's weights once, every live KV row once, the block's KV written once
+    dom_bytes = int(algorithmic_bytes(shape, n_layers, L_mid, BP) - 2 * shape.d_model * shape.vocab)
     dom_ms = total_ms / max(launches, 1)
     dom_gbps = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
 

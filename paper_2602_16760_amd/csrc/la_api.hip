@@ -314,6 +314,7 @@ extern "C" int la_kv_get_len(la_kv *kv, int *L_host, void *stream) {
   LA_HIP(hipStreamSynchronize((hipStream_t)stream));
   *L_host = v[0];
   kv->L_bound = v[0];
+  LA_REQUIRE((v[1] & 4) == 0, LA_EHIP, "a grid barrier timed out: the persistent kernel needs every workgroup resident at once");
   LA_REQUIRE(v[1] == 0, LA_ERANGE, "a block did not fit the cache (L + Bp > max_len) and was skipped");
   return LA_OK;
 }
