@@ -22,13 +22,23 @@
 //   loaded with the device-scope cache policy (sc1) so that no cache flush or invalidate is
 //   needed at a barrier: the barrier is a wait for the stores plus relaxed atomics.
 //
-// GEMM tasks.  A task is (slab, k-range).  Seven waves split the k-range, accumulate in
-// registers, and are summed through LDS in a fixed tree; the eighth wave runs the grid barrier
-// so that its polling loads never queue behind prefetched weights.  Tasks whose k-range is a
-// fraction of K write fp32 partials which the next small phase adds in a fixed order together
-// with the residual stream; it also emits the RMSNorm statistics and the operand fragments of
-// the next GEMM.  RMSNorm is applied as ((x * g) W) * rsqrt(mean(x^2) + eps), the row factor
-// after the contraction.  All reductions have a fixed order: results are run-to-run identical.
+// GEMM tasks.  A task is one slab with the whole contraction, so every task yields finished
+// outputs and its epilogue can apply what follows the product: the QKV epilogue scales by the
+// norm factor, rotates q and k (the packed column order puts channel i and i + dh/2 of a head
+// in the same slab), writes q as operand fragments and K, V into the cache; the O and down
+// epilogues add to the residual stream, emit the sum of squares of their columns and the
+// operand fragments of the next GEMM; the gate/up epilogue applies SwiGLU.  Seven waves split
+// the contraction, accumulate in registers and are summed through LDS in a fixed tree; the
+// eighth wave runs the grid barrier so that its polling never queues behind prefetched weights.
+// RMSNorm is applied as ((x * g) W) * rsqrt(mean(x^2) + eps), the row factor after the
+// contraction.  All reductions have a fixed order: results are run-to-run identical.
+//
+// Operand fragments and norm statistics live in buffers that are written once per launch
+// (one per layer and use), so a reader can never find a stale copy in its L2 and may load
+// them through the cache; only data read once (attention partials, q fragments, the block's
+// K/V rows) is loaded with sc1.
+#include <stdio.h>
+
 #include <algorithm>
 #include <new>
 
@@ -45,7 +55,6 @@ constexpr int WG_THREADS = 512;
 constexpr int NCW = 7;             // compute waves of a GEMM phase; wave 7 runs the grid barrier
 constexpr int MAX_T = 8;           // 16-column tiles per slab
 constexpr int MAX_MT = LA_MAX_ROWS / 16;
-constexpr int MAX_S = 8;           // k-splits across workgroups
 constexpr unsigned OOB = 0x80000000u;   // voffset beyond every buffer (all are < 2 GiB)
 constexpr unsigned RSRC_BYTES = 0x7fffffffu;
 constexpr int DEV = 16;            // cache policy sc1: device-scope coherent load / store
@@ -70,25 +79,22 @@ __device__ __forceinline__ Top top_merge2(Top a, Top b) {
 
 enum Phase {
   PH_PREP = 0,  // x -> operand fragments of the first QKV GEMM, norm statistics, RoPE table
-  PH_QKV,       // [q|k|v] partials
-  PH_QKVF,      // reduce partials, norm factor, RoPE, q fragments, K/V rows into the cache
+  PH_QKV,       // QKV GEMM; epilogue: norm factor, RoPE, q fragments, K/V rows into the cache
   PH_ATT,       // masked-block attention per (kv head, key split)
   PH_COMB,      // merge key splits -> operand fragments of the O GEMM
-  PH_O,         // attention output projection partials
-  PH_FO,        // x += partials; statistics; fragments for gate/up
+  PH_O,         // output projection; epilogue: x +=, statistics, fragments for gate/up
   PH_GU,        // gate/up GEMM + SwiGLU -> fragments for down
-  PH_DOWN,      // down projection partials
-  PH_FD,        // x += partials; statistics; fragments for the next layer's QKV
+  PH_DOWN,      // down projection; epilogue: x +=, statistics, fragments for the next layer
   PH_UPREP,     // final norm operand fragments
   PH_UGEMM,     // unembedding with per-slab arg-max
   PH_UFINAL     // arg-max over slabs
 };
-constexpr int PHASES_PER_LAYER = 9;
+constexpr int PHASES_PER_LAYER = 6;
 
-enum GemmMode { MODE_PARTIAL = 0, MODE_GATEUP = 1, MODE_UNEMBED = 2 };
+enum GemmMode { MODE_QKV = 0, MODE_RESID = 1, MODE_GATEUP = 2, MODE_UNEMBED = 3 };
 
 struct GemmDev {
-  int KT, T, n_slabs, S, N;
+  int KT, T, n_slabs, N;
 };
 
 struct LayerPtrs {
@@ -107,8 +113,10 @@ struct StackArgs {
   float *x;
   const int32_t *pos;
   const uint64_t *vis;
+  // write-once operand / statistics buffers, indexed by absolute layer (see frag_of)
   uint16_t *xa, *attn_a, *act_a, *qf;
-  float *part, *rsq, *o_part, *ml_part, *cs;
+  size_t xa_stride, attn_stride, act_stride, rsq_stride;  // elements per (layer, use)
+  float *rsq, *o_part, *ml_part, *cs;
   uint16_t *K, *V;
   size_t layer_elems;
   const int32_t *L_dev;
@@ -121,7 +129,13 @@ struct StackArgs {
   float *top2;
   unsigned *sync;
   unsigned epoch0, n_groups;
+  unsigned long long *trace;  // optional: 3 timestamps per phase from workgroup 0 (entry, after barrier, end)
+  size_t trace_wg_off;        // then per barrier and workgroup: arrival and release time
 };
+
+__device__ __forceinline__ void trace_mark(const StackArgs &a, int slot) {
+  if (a.trace && blockIdx.x == 0 && threadIdx.x == 0) a.trace[slot] = wall_clock64();
+}
 
 // ---- device-scope accessors ------------------------------------------------------------------
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const void *p) {
@@ -158,6 +172,8 @@ __device__ __forceinline__ void grid_arrive_wait(const StackArgs &a, unsigned ep
     unsigned g = blockIdx.x / SYNC_GROUP;
     unsigned gsize = (g + 1) * SYNC_GROUP <= n ? SYNC_GROUP : n - g * SYNC_GROUP;
     unsigned *gc = a.sync + SYNC_STRIDE * g, *top = a.sync + SYNC_STRIDE * 64, *rel = a.sync + SYNC_STRIDE * 65;
+    unsigned long long *tr = a.trace ? a.trace + a.trace_wg_off + ((size_t)(epoch - a.epoch0) * gridDim.x + blockIdx.x) * 2 : nullptr;
+    if (tr) tr[0] = wall_clock64();
     unsigned old = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old + 1 == epoch * gsize) {
       unsigned t = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -172,6 +188,7 @@ __device__ __forceinline__ void grid_arrive_wait(const StackArgs &a, unsigned ep
         break;
       }
     }
+    if (tr) tr[1] = wall_clock64();
   }
 }
 
@@ -202,16 +219,21 @@ __device__ __forceinline__ bool grid_barrier(const StackArgs &a, unsigned epoch,
 template <int MT, int T>
 struct Depth {  // k-tiles in flight per wave, bounded by the register file
   static constexpr int raw = (184 - 4 * MT * T) / (4 * (MT + T));
-  static constexpr int value = raw < 2 ? 2 : (raw > 6 ? 6 : raw);
+  static constexpr int value = raw < 2 ? 2 : (raw > 10 ? 10 : raw);
 };
 
 struct GemmIo {
   const uint16_t *W;
-  const uint16_t *A;
+  const uint16_t *A;      // operand fragments (a write-once buffer: loaded through the cache)
   int mode;
-  float *part;      // MODE_PARTIAL
-  uint16_t *act_a;  // MODE_GATEUP
-  Top *un_part;     // MODE_UNEMBED
+  const float *rsq_in;    // MODE_QKV, MODE_GATEUP: sums of squares of the input rows [64][ncg]
+  uint16_t *Kc, *Vc;      // MODE_QKV: this layer's cache
+  int L;
+  const float *gain;      // MODE_RESID: gain of the next norm (nullptr: no fragments wanted)
+  uint16_t *xa_out;       // MODE_RESID: fragments of x * gain for the next GEMM
+  float *rsq_out;         // MODE_RESID: sums of squares of the new x
+  uint16_t *act_a;        // MODE_GATEUP: fragments for the down projection
+  Top *un_part;           // MODE_UNEMBED
 };
 
 // One GEMM phase of this workgroup.  `epoch` != 0: run the grid barrier first, with the
@@ -222,7 +244,7 @@ __device__ __forceinline__ bool gemm_phase(const StackArgs &a, const GemmDev &g,
   constexpr int D = Depth<MT, T>::value;
   constexpr int LDT = 16 * T + 4;  // padded row length of the result tile in LDS
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int n_tasks = g.n_slabs * g.S;
+  const int n_tasks = g.n_slabs;
   __amdgpu_buffer_rsrc_t rw = rsrc_of(io.W), ra = rsrc_of(io.A);
   float *tile = (float *)lds;                         // [16 MT][LDT] after the tree
   float *rs_lds = (float *)(lds + 3 * MT * T * 64);   // [64] row factors (MODE_GATEUP)
@@ -232,11 +254,9 @@ __device__ __forceinline__ bool gemm_phase(const StackArgs &a, const GemmDev &g,
   bool first = true;
   for (int task = blockIdx.x; task < n_tasks || first; task += gridDim.x) {
     const bool live = task < n_tasks;
-    const int slab = live ? task / g.S : 0, ks = live ? task - slab * g.S : 0;
-    const int kt0 = (int)((long long)g.KT * ks / g.S), kt1 = (int)((long long)g.KT * (ks + 1) / g.S);
-    const int nk = kt1 - kt0;
+    const int slab = live ? task : 0;
     const int cw = wave < NCW ? wave : 0;
-    const int wk0 = kt0 + nk * cw / NCW, wk1 = kt0 + nk * (cw + 1) / NCW;
+    const int wk0 = g.KT * cw / NCW, wk1 = g.KT * (cw + 1) / NCW;
     const int n = (live && wave < NCW) ? wk1 - wk0 : 0;
     const unsigned w_base = (unsigned)(((size_t)slab * g.KT + wk0) * T * 1024);
     const unsigned a_base = (unsigned)wk0 * MT * 1024;
@@ -252,7 +272,7 @@ __device__ __forceinline__ bool gemm_phase(const StackArgs &a, const GemmDev &g,
       unsigned vo = (i < n) ? voff : OOB;
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        rA[slot][mt] = __builtin_amdgcn_raw_buffer_load_b128(ra, vo, a_base + (unsigned)(i * MT + mt) * 1024, DEV);
+        rA[slot][mt] = __builtin_amdgcn_raw_buffer_load_b128(ra, vo, a_base + (unsigned)(i * MT + mt) * 1024, 0);
     };
     // weights do not depend on the previous phase: request them before waiting at the barrier
 #pragma unroll
@@ -265,6 +285,7 @@ __device__ __forceinline__ bool gemm_phase(const StackArgs &a, const GemmDev &g,
       wg_barrier_raw();
       if (*dead) return false;
     }
+    if (first) trace_mark(a, 3 * (int)(epoch - a.epoch0) + 1);
     first = false;
     if (!live) break;
 #pragma unroll
@@ -272,15 +293,18 @@ __device__ __forceinline__ bool gemm_phase(const StackArgs &a, const GemmDev &g,
       load_a(s, s);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (io.mode == MODE_GATEUP && wave == NCW) {
-      // row factors rsqrt(mean(x^2) + eps) from the per-column-group partial sums
-      __amdgpu_buffer_rsrc_t rq = rsrc_of(a.rsq);
-      for (int r = 0; r < a.Bp; ++r) {
-        float s = 0.f;
-        for (int c = lane; c < a.ncg; c += 64) s += ld32f(rq, (unsigned)(r * a.ncg + c) * 4);
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        if (lane == 0) rs_lds[r] = 1.0f / sqrtf(s * a.inv_d + a.eps);
+    if ((io.mode == MODE_GATEUP || io.mode == MODE_QKV) && wave == NCW) {
+      // row factors rsqrt(mean(x^2) + eps) from the per-slab sums of squares: one row per
+      // lane, all loads independent of each other (ncg is a multiple of 4)
+      float s = 0.f;
+      if (lane < a.Bp) {
+        const f32x4 *rq = reinterpret_cast<const f32x4 *>(io.rsq_in + (size_t)lane * a.ncg);
+        for (int c4 = 0; c4 < a.ncg / 4; ++c4) {
+          f32x4 v = rq[c4];
+          s += (v[0] + v[1]) + (v[2] + v[3]);
+        }
       }
+      rs_lds[lane] = 1.0f / sqrtf(s * a.inv_d + a.eps);
     }
 
     f32x4 acc[MT][T];
@@ -335,14 +359,81 @@ __device__ __forceinline__ bool gemm_phase(const StackArgs &a, const GemmDev &g,
     }
     __syncthreads();
 
-    if (io.mode == MODE_PARTIAL) {
-      __amdgpu_buffer_rsrc_t rp = rsrc_of(io.part);
-      const int chunks = a.Bp * 4 * T;  // 16-byte pieces of the tile's live rows
-      for (int c = threadIdx.x; c < chunks; c += WG_THREADS) {
-        int row = c / (4 * T), c4 = c - row * 4 * T;
-        f32x4 v = *reinterpret_cast<const f32x4 *>(tile + row * LDT + 4 * c4);
-        st128(rp, (unsigned)((((size_t)ks * 64 + row) * g.N + (size_t)slab * 16 * T + 4 * c4) * 4),
-              __builtin_bit_cast(u32x4, v));
+    if (io.mode == MODE_QKV) {
+      // The slab holds channels 8j..8j+7 (columns 0..7) and dh/2 + 8j.. (columns 8..15) of one
+      // head: both members of every RoPE pair.  One thread per row.
+      const int b = threadIdx.x;
+      if (b < a.Bp) {
+        const int half = a.dh >> 1, spj = a.dh >> 4, grp = a.Hq / a.Hkv;
+        const int hs = slab / spj, j = slab - hs * spj;
+        const float rs = rs_lds[b];
+        const float *tr = tile + b * LDT;
+        const float qscale = hs < a.Hq ? 1.0f / sqrtf((float)a.dh) : 1.0f;
+        float y0[8], y1[8];
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+          float x0 = tr[w] * rs, x1 = tr[8 + w] * rs;
+          if (hs < a.Hq + a.Hkv) {
+            float c = a.cs[((size_t)b * half + 8 * j + w) * 2], sn = a.cs[((size_t)b * half + 8 * j + w) * 2 + 1];
+            y0[w] = (x0 * c - x1 * sn) * qscale;
+            y1[w] = (x1 * c + x0 * sn) * qscale;
+          } else {
+            y0[w] = x0;
+            y1[w] = x1;
+          }
+        }
+        u32x4 lo = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y0[4], y0[5]), pack_bf16(y0[6], y0[7])};
+        u32x4 hi = {pack_bf16(y1[0], y1[1]), pack_bf16(y1[2], y1[3]), pack_bf16(y1[4], y1[5]), pack_bf16(y1[6], y1[7])};
+        const int o_lo = j, o_hi = (half >> 3) + j;  // channel octets of the two pieces
+        if (hs < a.Hq) {
+          __amdgpu_buffer_rsrc_t rqf = rsrc_of(a.qf);
+          int kvh = hs / grp, jq = hs - kvh * grp, rt = jq * MT + (b >> 4);
+          size_t fb = ((size_t)kvh * (grp * MT) + rt) * (a.dh >> 5);
+          st128(rqf, (unsigned)(((fb + (o_lo >> 2)) * 64 + (b & 15) + 16 * (o_lo & 3)) * 16), lo);
+          st128(rqf, (unsigned)(((fb + (o_hi >> 2)) * 64 + (b & 15) + 16 * (o_hi & 3)) * 16), hi);
+        } else if (hs < a.Hq + a.Hkv) {
+          __amdgpu_buffer_rsrc_t rk = rsrc_of(io.Kc);
+          size_t rb = ((size_t)(io.L + b) * a.Hkv + (hs - a.Hq)) * a.dh;
+          st128(rk, (unsigned)((rb + 8 * o_lo) * 2), lo);
+          st128(rk, (unsigned)((rb + 8 * o_hi) * 2), hi);
+        } else {
+          __amdgpu_buffer_rsrc_t rv = rsrc_of(io.Vc);
+          int h = hs - a.Hq - a.Hkv;
+#pragma unroll
+          for (int w = 0; w < 8; ++w) {
+            st16(rv, (unsigned)(v_index(true, io.L + b, h, 8 * j + w, a.Hkv, a.dh) * 2), float_to_bf16(y0[w]));
+            st16(rv, (unsigned)(v_index(true, io.L + b, h, half + 8 * j + w, a.Hkv, a.dh) * 2), float_to_bf16(y1[w]));
+          }
+        }
+      }
+    } else if (io.mode == MODE_RESID) {
+      // x[:, slab columns] += tile; sum of squares of the new values; fragments of x * gain.
+      // Two threads per row, eight columns each.  This workgroup owns these columns of x in
+      // every layer, so x needs no device-scope accesses.
+      const int b = threadIdx.x >> 1, oct = threadIdx.x & 1;
+      if (b < a.Bp) {
+        const int col = 16 * slab + 8 * oct;
+        f32x4 *xp = reinterpret_cast<f32x4 *>(a.x + (size_t)b * a.d + col);
+        const float *tr = tile + b * LDT + 8 * oct;
+        f32x4 x0 = xp[0], x1 = xp[1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          x0[i] += tr[i];
+          x1[i] += tr[4 + i];
+        }
+        xp[0] = x0;
+        xp[1] = x1;
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
+        sq += __shfl_xor(sq, 1, 64);
+        if (io.gain) {
+          if (oct == 0) st32f(rsrc_of(io.rsq_out), (unsigned)(b * a.ncg + slab) * 4, sq);
+          const float *gp = io.gain + col;
+          u32x4 w = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
+                     pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+          st128(rsrc_of(io.xa_out), (unsigned)((((size_t)(col >> 5) * MT + (b >> 4)) * 64 + (b & 15) + 16 * ((col & 31) >> 3)) * 16), w);
+        }
       }
     } else if (io.mode == MODE_GATEUP) {
       // slab columns: 8T gate channels, then the same 8T channels of up
@@ -404,50 +495,28 @@ __device__ __forceinline__ bool gemm_dispatch(const StackArgs &a, const GemmDev 
   }
 }
 
-// ---- residual update, norm statistics, operand fragments -------------------------------------
-// Task = two groups of 32 columns (one per half of the workgroup): x += sum_s part[s] in a
-// fixed order; partial sum of squares per row over the group; bf16(x * gain) as fragments.
-__device__ __forceinline__ void finish_phase(const StackArgs &a, int S, int N, const float *gain, bool update_x) {
-  __amdgpu_buffer_rsrc_t rp = rsrc_of(a.part), rq = rsrc_of(a.rsq), rx = rsrc_of(a.xa);
+// ---- first operand of a launch: norm statistics and fragments of x * gain ----------------------
+// Task = two groups of 32 columns (one per half of the workgroup).  Sums of squares are kept per
+// 16 columns, the granularity of the GEMM epilogues that produce them in later phases.
+__device__ __forceinline__ void prep_phase(const StackArgs &a, const float *gain, uint16_t *xa_out, float *rsq_out) {
+  __amdgpu_buffer_rsrc_t rq = rsrc_of(rsq_out), rx = rsrc_of(xa_out);
   const int sub = threadIdx.x >> 8, r = (threadIdx.x & 255) >> 2, oct = threadIdx.x & 3;
-  for (int task = blockIdx.x; task * 2 < a.ncg; task += gridDim.x) {
+  const int n_cg = a.d / 32;
+  for (int task = blockIdx.x; task * 2 < n_cg; task += gridDim.x) {
     int cg = task * 2 + sub;
-    if (cg >= a.ncg || r >= a.Bp) continue;
+    if (cg >= n_cg || r >= a.Bp) continue;
     int c0 = cg * 32 + oct * 8;
-    float v[8];
     const f32x4 *xp = reinterpret_cast<const f32x4 *>(a.x + (size_t)r * a.d + c0);
     f32x4 x0 = xp[0], x1 = xp[1];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      v[i] = x0[i];
-      v[4 + i] = x1[i];
-    }
-    for (int s = 0; s < S; ++s) {
-      unsigned o = (unsigned)((((size_t)s * 64 + r) * N + c0) * 4);
-      f32x4 p0 = __builtin_bit_cast(f32x4, ld128(rp, o)), p1 = __builtin_bit_cast(f32x4, ld128(rp, o + 16));
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        v[i] += p0[i];
-        v[4 + i] += p1[i];
-      }
-    }
-    if (update_x) {
-      f32x4 *xo = reinterpret_cast<f32x4 *>(a.x + (size_t)r * a.d + c0);
-      xo[0] = f32x4{v[0], v[1], v[2], v[3]};
-      xo[1] = f32x4{v[4], v[5], v[6], v[7]};
-    }
     float sq = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
+    for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
     sq += __shfl_xor(sq, 1, 64);
-    sq += __shfl_xor(sq, 2, 64);
-    if (oct == 0) st32f(rq, (unsigned)(r * a.ncg + cg) * 4, sq);
-    if (gain) {
-      u32x4 w;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) w[i] = pack_bf16(v[2 * i] * gain[c0 + 2 * i], v[2 * i + 1] * gain[c0 + 2 * i + 1]);
-      st128(rx, (unsigned)((((size_t)cg * a.MT + (r >> 4)) * 64 + (r & 15) + 16 * oct) * 16), w);
-    }
+    if ((oct & 1) == 0) st32f(rq, (unsigned)(r * a.ncg + 2 * cg + (oct >> 1)) * 4, sq);
+    const float *gp = gain + c0;
+    u32x4 w = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
+               pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+    st128(rx, (unsigned)((((size_t)cg * a.MT + (r >> 4)) * 64 + (r & 15) + 16 * oct) * 16), w);
   }
 }
 
@@ -462,62 +531,6 @@ __device__ __forceinline__ void rope_table_phase(const StackArgs &a) {
     sincos((double)a.pos[b] * inv, &s, &c);
     st32f(rc, (unsigned)e * 8, (float)c);
     st32f(rc, (unsigned)e * 8 + 4, (float)s);
-  }
-}
-
-// ---- QKV epilogue: one wave per (row, head slot) ------------------------------------------------
-// q fragments: [kv head][q-row tile][dh k-tile][lane][8], q-row = j * 16 MT + b for the j-th
-// query head of the group, pre-multiplied by 1/sqrt(dh).  Keys are cached after rotation.
-__device__ __forceinline__ void qkvf_phase(const StackArgs &a, int S, uint16_t *Kc, uint16_t *Vc, int L,
-                                           uint16_t *stage_all) {
-  __amdgpu_buffer_rsrc_t rp = rsrc_of(a.part), rq = rsrc_of(a.rsq), rc = rsrc_of(a.cs), rqf = rsrc_of(a.qf),
-                         rk = rsrc_of(Kc), rv = rsrc_of(Vc);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  uint16_t *stage = stage_all + wave * 256;
-  const int nh = a.Hq + 2 * a.Hkv, n_units = a.Bp * nh, half = a.dh >> 1, g = a.Hq / a.Hkv;
-  const int N = a.qkv.N;
-  for (int u = blockIdx.x * 8 + wave; u < n_units; u += gridDim.x * 8) {
-    int b = u / nh, hs = u - b * nh;
-    float s = 0.f;
-    for (int c = lane; c < a.ncg; c += 64) s += ld32f(rq, (unsigned)(b * a.ncg + c) * 4);
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    float rs = 1.0f / sqrtf(s * a.inv_d + a.eps);
-    int col0 = hs * a.dh;
-    auto val = [&](int c) {
-      float t = 0.f;
-      for (int k = 0; k < S; ++k) t += ld32f(rp, (unsigned)((((size_t)k * 64 + b) * N + col0 + c) * 4));
-      return t * rs;
-    };
-    if (hs < a.Hq + a.Hkv) {
-      float qscale = hs < a.Hq ? 1.0f / sqrtf((float)a.dh) : 1.0f;
-      if (lane < half) {
-        float c = ld32f(rc, (unsigned)(b * half + lane) * 8), sn = ld32f(rc, (unsigned)(b * half + lane) * 8 + 4);
-        float x0 = val(lane), x1 = val(lane + half);
-        stage[lane] = float_to_bf16((x0 * c - x1 * sn) * qscale);
-        stage[lane + half] = float_to_bf16((x1 * c + x0 * sn) * qscale);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      if (lane < a.dh / 8) {  // one 16-byte piece of 8 channels per lane
-        u32x4 w = *reinterpret_cast<const u32x4 *>(stage + 8 * lane);
-        if (hs < a.Hq) {
-          int kvh = hs / g, j = hs - kvh * g;
-          int rt = j * a.MT + (b >> 4);
-          unsigned o = (unsigned)(((((size_t)kvh * (g * a.MT) + rt) * (a.dh >> 5) + (lane >> 2)) * 64 + (b & 15) + 16 * (lane & 3)) * 16);
-          st128(rqf, o, w);
-        } else {
-          st128(rk, (unsigned)((((size_t)(L + b) * a.Hkv + (hs - a.Hq)) * a.dh + 8 * lane) * 2), w);
-        }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    } else {
-      int h = hs - a.Hq - a.Hkv;
-      for (int c = lane; c < a.dh; c += 64)
-        st16(rv, (unsigned)(v_index(true, L + b, h, c, a.Hkv, a.dh) * 2), float_to_bf16(val(c)));
-    }
   }
 }
 
@@ -552,17 +565,28 @@ __device__ __forceinline__ void attention_phase(const StackArgs &a, const uint16
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
       float m_run = -1e30f, l_run = 0.f;
-      for (int kb = kb0; kb < kb1; ++kb) {
-        const unsigned k_off = (unsigned)((((size_t)(kb * 32 + c16) * a.Hkv + kvh) * DH + 8 * q4) * 2);
-        const unsigned v_off = (unsigned)(((((size_t)kb * a.Hkv + kvh) * DH + c16) * 32 + 8 * q4) * 2);
-        u32x4 ka[KT], kbv[KT], vt[DT];
+      u32x4 ka[KT], kbv[KT], vt[DT], nka[KT], nkbv[KT], nvt[DT];
+      auto load_kv = [&](int kb, u32x4 *pa, u32x4 *pb, u32x4 *pv) {
+        const unsigned k_off = kb < kb1 ? (unsigned)((((size_t)(kb * 32 + c16) * a.Hkv + kvh) * DH + 8 * q4) * 2) : OOB;
+        const unsigned v_off = kb < kb1 ? (unsigned)(((((size_t)kb * a.Hkv + kvh) * DH + c16) * 32 + 8 * q4) * 2) : OOB;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
-          ka[kt] = ld128(rk, k_off + kt * 64);
-          kbv[kt] = ld128(rk, k_off + (unsigned)(16 * a.Hkv * DH * 2) + kt * 64);
+          pa[kt] = ld128(rk, k_off + kt * 64);
+          pb[kt] = ld128(rk, k_off + (unsigned)(16 * a.Hkv * DH * 2) + kt * 64);
         }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) vt[dt] = ld128(rv, v_off + dt * 16 * 32 * 2);
+        for (int dt = 0; dt < DT; ++dt) pv[dt] = ld128(rv, v_off + dt * 16 * 32 * 2);
+      };
+      load_kv(kb0, nka, nkbv, nvt);
+      for (int kb = kb0; kb < kb1; ++kb) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+          ka[kt] = nka[kt];
+          kbv[kt] = nkbv[kt];
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vt[dt] = nvt[dt];
+        load_kv(kb + 1, nka, nkbv, nvt);  // the next block's tiles travel while this one is used
         f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
@@ -602,13 +626,11 @@ __device__ __forceinline__ void attention_phase(const StackArgs &a, const uint16
           o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[dt]), pb, o[dt], 0, 0, 0);
         }
       }
-      // o[dt][i] = O^T[channel 16 dt + 4 q4 + i][q-row rt*16 + c16]
-      size_t base = ((size_t)kvh * a.ns + split) * DH * QR;
+      // o[dt][i] = O^T[channel 16 dt + 4 q4 + i][q-row rt*16 + c16]; partials are stored
+      // [kv head][split][q-row][channel]: 16 bytes per lane and store
+      size_t base = (((size_t)kvh * a.ns + split) * QR + rt * 16 + c16) * DH;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          st32f(ro, (unsigned)((base + (size_t)(16 * dt + 4 * q4 + i) * QR + rt * 16 + c16) * 4), o[dt][i]);
+      for (int dt = 0; dt < DT; ++dt) st128(ro, (unsigned)((base + 16 * dt + 4 * q4) * 4), __builtin_bit_cast(u32x4, o[dt]));
       if (q4 == 0) {
         unsigned mo = (unsigned)(((((size_t)kvh * a.ns + split) * QR + rt * 16 + c16) * 2) * 4);
         st32f(rm, mo, m_run);
@@ -621,8 +643,8 @@ __device__ __forceinline__ void attention_phase(const StackArgs &a, const uint16
 // Merge the key splits; write the attention output as operand fragments of the O GEMM.
 // Task = (kv head, q-row tile) per half workgroup: 16 q-rows x DH/8 channel octets.
 template <int DH>
-__device__ __forceinline__ void combine_phase(const StackArgs &a) {
-  __amdgpu_buffer_rsrc_t ro = rsrc_of(a.o_part), rm = rsrc_of(a.ml_part), ra = rsrc_of(a.attn_a);
+__device__ __forceinline__ void combine_phase(const StackArgs &a, uint16_t *attn_out) {
+  __amdgpu_buffer_rsrc_t ro = rsrc_of(a.o_part), rm = rsrc_of(a.ml_part), ra = rsrc_of(attn_out);
   const int g = a.Hq / a.Hkv, n_rt = g * a.MT, QR = n_rt * 16, n_units = a.Hkv * n_rt;
   const int sub = threadIdx.x >> 8, t = threadIdx.x & 255, rr = t & 15, oct = t >> 4;
   for (int task = blockIdx.x; task * 2 < n_units; task += gridDim.x) {
@@ -631,16 +653,35 @@ __device__ __forceinline__ void combine_phase(const StackArgs &a) {
     int kvh = u / n_rt, rt = u - kvh * n_rt;
     int r = rt * 16 + rr, b = (rt % a.MT) * 16 + rr, j = rt / a.MT;
     if (b >= a.Bp) continue;
-    float M = -1e30f;
-    for (int s = 0; s < a.ns; ++s) M = fmaxf(M, ld32f(rm, (unsigned)(((((size_t)kvh * a.ns + s) * QR + r) * 2) * 4)));
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, lsum = 0.f;
-    for (int s = 0; s < a.ns; ++s) {
-      unsigned mo = (unsigned)(((((size_t)kvh * a.ns + s) * QR + r) * 2) * 4);
-      float w = __expf(ld32f(rm, mo) - M);
-      lsum += w * ld32f(rm, mo + 4);
-      size_t ob = ((size_t)kvh * a.ns + s) * DH * QR + (size_t)(oct * 8) * QR + r;
+    // online merge in split order; loads of eight splits are issued together
+    float M = -1e30f, lsum = 0.f;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < a.ns; s0 += 8) {
+      float ms[8], ls[8];
+      f32x4 lo[8], hi[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] += w * ld32f(ro, (unsigned)((ob + (size_t)i * QR) * 4));
+      for (int k = 0; k < 8; ++k) {
+        int sp = min(s0 + k, a.ns - 1);
+        size_t row = ((size_t)kvh * a.ns + sp) * QR + r;
+        ms[k] = ld32f(rm, (unsigned)(row * 8));
+        ls[k] = ld32f(rm, (unsigned)(row * 8 + 4));
+        lo[k] = __builtin_bit_cast(f32x4, ld128(ro, (unsigned)((row * DH + oct * 8) * 4)));
+        hi[k] = __builtin_bit_cast(f32x4, ld128(ro, (unsigned)((row * DH + oct * 8 + 4) * 4)));
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (s0 + k < a.ns) {
+          float m_new = fmaxf(M, ms[k]);
+          float c_old = __expf(M - m_new), c_new = __expf(ms[k] - m_new);
+          lsum = lsum * c_old + ls[k] * c_new;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            acc[i] = acc[i] * c_old + lo[k][i] * c_new;
+            acc[4 + i] = acc[4 + i] * c_old + hi[k][i] * c_new;
+          }
+          M = m_new;
+        }
+      }
     }
     float inv = 1.0f / lsum;
     int col = (kvh * g + j) * DH + oct * 8;
@@ -652,7 +693,7 @@ __device__ __forceinline__ void combine_phase(const StackArgs &a) {
 
 // Arg-max over the slabs' partial results; logits carry the row's norm factor from here on.
 __device__ __forceinline__ void unembed_final_phase(const StackArgs &a, Top *red) {
-  __amdgpu_buffer_rsrc_t ru = rsrc_of(a.un_part), rq = rsrc_of(a.rsq);
+  __amdgpu_buffer_rsrc_t ru = rsrc_of(a.un_part);
   const int sub = threadIdx.x >> 8, t = threadIdx.x & 255;
   for (int task = blockIdx.x; task * 2 < a.Bp; task += gridDim.x) {
     int b = task * 2 + sub;
@@ -671,7 +712,7 @@ __device__ __forceinline__ void unembed_final_phase(const StackArgs &a, Top *red
     }
     if (t < 64 && b < a.Bp) {
       float s = 0.f;
-      for (int c = t; c < a.ncg; c += 64) s += ld32f(rq, (unsigned)(b * a.ncg + c) * 4);
+      for (int c = t; c < a.ncg; c += 64) s += a.rsq[(size_t)b * a.ncg + c];
       for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
       if (t == 0) {
         float rs = 1.0f / sqrtf(s * a.inv_d + a.eps);
@@ -711,64 +752,73 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
       ph = PH_QKV + (p - 1) % PHASES_PER_LAYER;
     }
     uint16_t *Kc = a.K + (size_t)layer * a.layer_elems, *Vc = a.V + (size_t)layer * a.layer_elems;
+    // write-once buffers of this layer: fragments of the attn-norm and mlp-norm inputs with
+    // their statistics, the attention output, the SwiGLU output
+    uint16_t *xa0 = a.xa + (size_t)(2 * layer) * a.xa_stride, *xa1 = xa0 + a.xa_stride;
+    float *rsq0 = a.rsq + (size_t)(2 * layer) * a.rsq_stride, *rsq1 = rsq0 + a.rsq_stride;
+    uint16_t *attn_l = a.attn_a + (size_t)layer * a.attn_stride, *act_l = a.act_a + (size_t)layer * a.act_stride;
     const bool is_gemm = ph == PH_QKV || ph == PH_O || ph == PH_GU || ph == PH_DOWN || ph == PH_UGEMM;
+    trace_mark(a, 3 * (p - a.p_begin));
     if (epoch && !is_gemm && !grid_barrier(a, epoch, &dead)) return;
+    if (!is_gemm) trace_mark(a, 3 * (p - a.p_begin) + 1);
+    GemmIo io{};
     switch (ph) {
       case PH_PREP:
-        finish_phase(a, 0, 0, a.layers[layer].g_attn, false);
+        prep_phase(a, a.layers[layer].g_attn, xa0, rsq0);
         rope_table_phase(a);
         break;
       case PH_QKV:
-        if (!gemm_dispatch<MT>(a, a.qkv, GemmIo{a.layers[layer].wqkv, a.xa, MODE_PARTIAL, a.part, nullptr, nullptr}, epoch, lds, &dead)) return;
-        break;
-      case PH_QKVF:
-        qkvf_phase(a, a.qkv.S, Kc, Vc, L, (uint16_t *)lds);
+        io.W = a.layers[layer].wqkv; io.A = xa0; io.mode = MODE_QKV; io.rsq_in = rsq0; io.Kc = Kc; io.Vc = Vc; io.L = L;
+        if (!gemm_dispatch<MT>(a, a.qkv, io, epoch, lds, &dead)) return;
         break;
       case PH_ATT:
         if (a.dh == 128) attention_phase<128>(a, Kc, Vc, L);
         else attention_phase<64>(a, Kc, Vc, L);
         break;
       case PH_COMB:
-        if (a.dh == 128) combine_phase<128>(a);
-        else combine_phase<64>(a);
+        if (a.dh == 128) combine_phase<128>(a, attn_l);
+        else combine_phase<64>(a, attn_l);
         break;
       case PH_O:
-        if (!gemm_dispatch<MT>(a, a.o, GemmIo{a.layers[layer].wo, a.attn_a, MODE_PARTIAL, a.part, nullptr, nullptr}, epoch, lds, &dead)) return;
-        break;
-      case PH_FO:
-        finish_phase(a, a.o.S, a.o.N, a.layers[layer].g_mlp, true);
+        io.W = a.layers[layer].wo; io.A = attn_l; io.mode = MODE_RESID; io.gain = a.layers[layer].g_mlp; io.xa_out = xa1; io.rsq_out = rsq1;
+        if (!gemm_dispatch<MT>(a, a.o, io, epoch, lds, &dead)) return;
         break;
       case PH_GU:
-        if (!gemm_dispatch<MT>(a, a.gu, GemmIo{a.layers[layer].wgu, a.xa, MODE_GATEUP, nullptr, a.act_a, nullptr}, epoch, lds, &dead)) return;
+        io.W = a.layers[layer].wgu; io.A = xa1; io.mode = MODE_GATEUP; io.rsq_in = rsq1; io.act_a = act_l;
+        if (!gemm_dispatch<MT>(a, a.gu, io, epoch, lds, &dead)) return;
         break;
       case PH_DOWN:
-        if (!gemm_dispatch<MT>(a, a.down, GemmIo{a.layers[layer].wdown, a.act_a, MODE_PARTIAL, a.part, nullptr, nullptr}, epoch, lds, &dead)) return;
-        break;
-      case PH_FD:
         // the fragments feed the next layer's QKV GEMM; the last layer of the call needs none
-        finish_phase(a, a.down.S, a.down.N, layer + 1 < a.le ? a.layers[layer + 1].g_attn : nullptr, true);
+        io.W = a.layers[layer].wdown; io.A = act_l; io.mode = MODE_RESID;
+        io.gain = layer + 1 < a.le ? a.layers[layer + 1].g_attn : nullptr;
+        io.xa_out = xa0 + 2 * a.xa_stride; io.rsq_out = rsq0 + 2 * a.rsq_stride;
+        if (!gemm_dispatch<MT>(a, a.down, io, epoch, lds, &dead)) return;
         break;
       case PH_UPREP:
-        finish_phase(a, 0, 0, a.g_final, false);
+        prep_phase(a, a.g_final, a.xa, a.rsq);
         break;
       case PH_UGEMM:
-        if (!gemm_dispatch<MT>(a, a.un, GemmIo{a.un_w, a.xa, MODE_UNEMBED, nullptr, nullptr, a.un_part}, epoch, lds, &dead)) return;
+        io.W = a.un_w; io.A = a.xa; io.mode = MODE_UNEMBED; io.un_part = a.un_part;
+        if (!gemm_dispatch<MT>(a, a.un, io, epoch, lds, &dead)) return;
         break;
       case PH_UFINAL:
         unembed_final_phase(a, (Top *)lds);
         break;
     }
+    trace_mark(a, 3 * (p - a.p_begin) + 2);
   }
 }
 
 // ---- weight packing (once, at model set-up) -----------------------------------------------------
 // Packed column pc of the destination -> (source matrix, source column).
-//   kind 0: one source [K, N];  kind 1: q | k | v concatenation;
+//   kind 0: one source [K, N];
+//   kind 1: q | k | v heads; each 16-column slab holds channels 8j..8j+7 and dh/2+8j.. of one
+//           head, i.e. both members of eight RoPE pairs (slabs are one tile wide);
 //   kind 2: per slab, 8T gate channels followed by the same 8T channels of up.
 struct PackSrc {
   const uint16_t *s0, *s1, *s2;
   int n0, n1, n2;
-  int kind, T, F;
+  int kind, T, F, dh;
 };
 __device__ __forceinline__ const uint16_t *pack_col(const PackSrc &p, int pc, int &ld) {
   if (p.kind == 0) {
@@ -776,6 +826,9 @@ __device__ __forceinline__ const uint16_t *pack_col(const PackSrc &p, int pc, in
     return p.s0 + pc;
   }
   if (p.kind == 1) {
+    int slab = pc >> 4, w = pc & 15, spj = p.dh >> 4;
+    int hs = slab / spj, j = slab - hs * spj;
+    pc = hs * p.dh + (w < 8 ? 8 * j + w : (p.dh >> 1) + 8 * j + (w - 8));
     if (pc < p.n0) { ld = p.n0; return p.s0 + pc; }
     pc -= p.n0;
     if (pc < p.n1) { ld = p.n1; return p.s1 + pc; }
@@ -836,13 +889,15 @@ struct MfmaModel {
   LayerPtrs *dev_ptrs = nullptr;
   bool ptrs_dirty = true;
   uint16_t *un = nullptr;
-  uint16_t *xa = nullptr, *attn_a = nullptr, *act_a = nullptr, *qf = nullptr;
-  float *part = nullptr, *rsq = nullptr, *o_part = nullptr, *ml_part = nullptr;
+  uint16_t *xa = nullptr, *attn_a = nullptr, *act_a = nullptr, *qf = nullptr;  // per layer (and use)
+  uint16_t *xa_u = nullptr;                                                    // unembedding input
+  float *rsq = nullptr, *rsq_u = nullptr, *o_part = nullptr, *ml_part = nullptr;
   Top *un_part = nullptr;
   unsigned *sync = nullptr;
   int32_t *zero_len = nullptr;  // {0, scratch error word}: the unembedding has no cache to overflow
   unsigned epoch = 0;
   int max_ns = 32;
+  unsigned long long *trace = nullptr;  // LA_TRACE=1: per-phase timestamps, printed after each launch
 };
 
 static int env_int(const char *name, int dflt) {
@@ -850,8 +905,8 @@ static int env_int(const char *name, int dflt) {
   return (v && *v) ? atoi(v) : dflt;
 }
 
-// Tiles per slab: the slab count times a k-split of 1, 2, 4 or 8 should fill the CUs in whole
-// rounds, and wide slabs are preferred (fewer activation re-reads per weight byte).
+// Tiles per slab for the gate/up and unembedding GEMMs: the slab count should fill the CUs in
+// whole rounds, and wide slabs are preferred (fewer operand re-reads per weight byte).
 static GemmPlan make_plan(int N, int K, int n_wgs, bool gateup, int F, const char *env) {
   GemmPlan p;
   p.N = N; p.K = K; p.KT = K / 32;
@@ -859,13 +914,9 @@ static GemmPlan make_plan(int N, int K, int n_wgs, bool gateup, int F, const cha
   double best = 1e300;
   for (int T = MAX_T; T >= 1; --T) {
     if (gateup ? (F % (8 * T) != 0) : (tiles % T != 0)) continue;
-    int slabs = tiles / T;
-    for (int S = 1; S <= MAX_S; S *= 2) {
-      if (p.KT / S < NCW && S > 1) continue;
-      int rounds = ceil_div(slabs * S, n_wgs);
-      double cost = (double)rounds * ceil_div(p.KT, S) * (T + 2.0) + 6.0 * S;
-      if (cost < best) { best = cost; p.T = T; }
-    }
+    int rounds = ceil_div(tiles / T, n_wgs);
+    double cost = (double)rounds * (T + 2.0);  // per k-tile: T weight fragments + ~2 operand fragments
+    if (cost < best) { best = cost; p.T = T; }
   }
   int forced = env_int(env, 0);
   if (forced >= 1 && forced <= MAX_T && (gateup ? (F % (8 * forced) == 0) : (tiles % forced == 0))) p.T = forced;
@@ -874,23 +925,16 @@ static GemmPlan make_plan(int N, int K, int n_wgs, bool gateup, int F, const cha
   return p;
 }
 
-static int choose_split(const GemmPlan &p, int n_wgs, int MT, const char *env) {
-  int best_S = 1;
-  double best = 1e300;
-  for (int S = 1; S <= MAX_S; S *= 2) {
-    if (p.KT / S < NCW && S > 1) continue;
-    int rounds = ceil_div(p.n_slabs * S, n_wgs);
-    double cost = (double)rounds * ceil_div(p.KT, S) * (p.T + MT) + 6.0 * S;
-    if (cost < best) { best = cost; best_S = S; }
-  }
-  int forced = env_int(env, 0);
-  if (forced >= 1 && forced <= MAX_S && p.KT / forced >= 1) best_S = forced;
-  return best_S;
+static GemmPlan slab1_plan(int N, int K) {  // one 16-column tile per slab: the epilogue-fused GEMMs
+  GemmPlan p;
+  p.N = N; p.K = K; p.KT = K / 32; p.T = 1; p.n_slabs = N / 16;
+  p.bytes = (size_t)N * K * 2;
+  return p;
 }
 
 int mfma_supported(const la_model_desc *d) {
   int qd = d->n_q_heads * d->head_dim, nqkv = (d->n_q_heads + 2 * d->n_kv_heads) * d->head_dim;
-  if (d->d_model % 32 || qd % 32 || d->d_ffn % 32 || nqkv % 16 || d->vocab % 16) return 0;
+  if (d->d_model % 128 || qd % 32 || d->d_ffn % 32 || nqkv % 16 || d->vocab % 16) return 0;
   if (d->head_dim != 64 && d->head_dim != 128) return 0;
   if (d->n_q_heads / d->n_kv_heads > 8) return 0;
   // packed matrices and scratch are addressed through 32-bit buffer offsets
@@ -913,8 +957,8 @@ void mfma_destroy(la_model *m) {
     for (void *p : ps)
       if (p) (void)hipFree(p);
   }
-  void *ps[] = {f->un, f->xa, f->attn_a, f->act_a, f->qf, f->part, f->rsq, f->o_part, f->ml_part, f->un_part,
-                f->sync, f->dev_ptrs, f->zero_len};
+  void *ps[] = {f->un, f->xa, f->attn_a, f->act_a, f->qf, f->xa_u, f->rsq_u, f->rsq, f->o_part, f->ml_part, f->un_part,
+                f->sync, f->dev_ptrs, f->zero_len, f->trace};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   delete f;
@@ -932,25 +976,26 @@ int mfma_create(la_model *m) {
   f->n_wgs = std::min(env_int("LA_WGS", cus), cus);  // one resident workgroup per CU: the barrier needs co-residency
   f->persistent = env_int("LA_PERSISTENT", 1) != 0;
   int qd = m->qdim(), nqkv = m->nqkv(), g = d.n_q_heads / d.n_kv_heads;
-  f->p_qkv = make_plan(nqkv, d.d_model, f->n_wgs, false, 0, "LA_T_QKV");
-  f->p_o = make_plan(d.d_model, qd, f->n_wgs, false, 0, "LA_T_O");
+  f->p_qkv = slab1_plan(nqkv, d.d_model);
+  f->p_o = slab1_plan(d.d_model, qd);
   f->p_gu = make_plan(2 * d.d_ffn, d.d_model, f->n_wgs, true, d.d_ffn, "LA_T_GU");
-  f->p_down = make_plan(d.d_model, d.d_ffn, f->n_wgs, false, 0, "LA_T_DOWN");
+  f->p_down = slab1_plan(d.d_model, d.d_ffn);
   f->p_un = make_plan(d.vocab, d.d_model, f->n_wgs, false, 0, "LA_T_UN");
   f->layers.resize(d.n_layers);
   f->host_ptrs.resize(d.n_layers);
-  size_t R = LA_MAX_ROWS;
-  int n_max = std::max(nqkv, d.d_model);
+  size_t R = LA_MAX_ROWS, nl = d.n_layers;
   f->max_ns = std::max(1, std::min(64, f->n_wgs / d.n_kv_heads));
   size_t QR = (size_t)g * MAX_MT * 16;
   int n_sync = SYNC_STRIDE * 66;
+  size_t ncg = d.d_model / 16;
   bool ok = true;
-  ok = ok && (f->xa = (uint16_t *)dalloc(R * d.d_model * 2));
-  ok = ok && (f->attn_a = (uint16_t *)dalloc(R * qd * 2));
-  ok = ok && (f->act_a = (uint16_t *)dalloc(R * (size_t)d.d_ffn * 2));
+  ok = ok && (f->xa = (uint16_t *)dalloc(2 * nl * R * d.d_model * 2));
+  ok = ok && (f->attn_a = (uint16_t *)dalloc(nl * R * qd * 2));
+  ok = ok && (f->act_a = (uint16_t *)dalloc(nl * R * (size_t)d.d_ffn * 2));
+  ok = ok && (f->xa_u = (uint16_t *)dalloc(R * d.d_model * 2));
   ok = ok && (f->qf = (uint16_t *)dalloc((size_t)d.n_kv_heads * QR * d.head_dim * 2));
-  ok = ok && (f->part = (float *)dalloc((size_t)MAX_S * R * n_max * 4));
-  ok = ok && (f->rsq = (float *)dalloc((size_t)(d.d_model / 32) * 64 * 4));
+  ok = ok && (f->rsq = (float *)dalloc(2 * nl * R * ncg * 4));
+  ok = ok && (f->rsq_u = (float *)dalloc(R * ncg * 4));
   ok = ok && (f->o_part = (float *)dalloc((size_t)d.n_kv_heads * f->max_ns * QR * d.head_dim * 4));
   ok = ok && (f->ml_part = (float *)dalloc((size_t)d.n_kv_heads * f->max_ns * QR * 2 * 4));
   ok = ok && (f->sync = (unsigned *)dalloc((size_t)n_sync * 4));
@@ -958,12 +1003,18 @@ int mfma_create(la_model *m) {
   ok = ok && (f->zero_len = (int32_t *)dalloc(8));
   LA_REQUIRE(ok, LA_ENOMEM, "device allocation failed in the MFMA path");
   // pad rows of the operand buffers are read by the MFMAs: keep them finite
-  LA_HIP(hipMemset(f->xa, 0, R * d.d_model * 2));
-  LA_HIP(hipMemset(f->attn_a, 0, R * qd * 2));
-  LA_HIP(hipMemset(f->act_a, 0, R * (size_t)d.d_ffn * 2));
+  LA_HIP(hipMemset(f->xa, 0, 2 * nl * R * d.d_model * 2));
+  LA_HIP(hipMemset(f->attn_a, 0, nl * R * qd * 2));
+  LA_HIP(hipMemset(f->act_a, 0, nl * R * (size_t)d.d_ffn * 2));
+  LA_HIP(hipMemset(f->xa_u, 0, R * d.d_model * 2));
   LA_HIP(hipMemset(f->qf, 0, (size_t)d.n_kv_heads * QR * d.head_dim * 2));
   LA_HIP(hipMemset(f->sync, 0, (size_t)n_sync * 4));
   LA_HIP(hipMemset(f->zero_len, 0, 8));
+  if (env_int("LA_TRACE", 0)) {
+    size_t np = 2 + PHASES_PER_LAYER * d.n_layers;
+    f->trace = (unsigned long long *)dalloc((3 * np + 2 * np * f->n_wgs) * 8);
+    LA_REQUIRE(f->trace != nullptr, LA_ENOMEM, "device allocation failed");
+  }
   return LA_OK;
 }
 
@@ -982,13 +1033,13 @@ int mfma_set_layer(la_model *m, int layer, const la_layer_weights *w, hipStream_
   int qd = m->qdim(), kvd = m->kvdim();
   const la_model_desc &d = m->d;
   int rc;
-  PackSrc q{(const uint16_t *)w->wq, (const uint16_t *)w->wk, (const uint16_t *)w->wv, qd, kvd, kvd, 1, f->p_qkv.T, 0};
+  PackSrc q{(const uint16_t *)w->wq, (const uint16_t *)w->wk, (const uint16_t *)w->wv, qd, kvd, kvd, 1, f->p_qkv.T, 0, d.head_dim};
   if ((rc = pack(q, f->p_qkv, &l.wqkv, s))) return rc;
-  PackSrc o{(const uint16_t *)w->wo, nullptr, nullptr, d.d_model, 0, 0, 0, f->p_o.T, 0};
+  PackSrc o{(const uint16_t *)w->wo, nullptr, nullptr, d.d_model, 0, 0, 0, f->p_o.T, 0, 0};
   if ((rc = pack(o, f->p_o, &l.wo, s))) return rc;
-  PackSrc gu{(const uint16_t *)w->wgate, (const uint16_t *)w->wup, nullptr, d.d_ffn, d.d_ffn, 0, 2, f->p_gu.T, d.d_ffn};
+  PackSrc gu{(const uint16_t *)w->wgate, (const uint16_t *)w->wup, nullptr, d.d_ffn, d.d_ffn, 0, 2, f->p_gu.T, d.d_ffn, 0};
   if ((rc = pack(gu, f->p_gu, &l.wgu, s))) return rc;
-  PackSrc dn{(const uint16_t *)w->wdown, nullptr, nullptr, d.d_model, 0, 0, 0, f->p_down.T, 0};
+  PackSrc dn{(const uint16_t *)w->wdown, nullptr, nullptr, d.d_model, 0, 0, 0, f->p_down.T, 0, 0};
   if ((rc = pack(dn, f->p_down, &l.wdown, s))) return rc;
   f->host_ptrs[layer] = LayerPtrs{l.wqkv, l.wo, l.wgu, l.wdown, m->layers[layer].g_attn, m->layers[layer].g_mlp};
   f->ptrs_dirty = true;
@@ -997,7 +1048,7 @@ int mfma_set_layer(la_model *m, int layer, const la_layer_weights *w, hipStream_
 
 int mfma_set_head(la_model *m, const void *unembed, hipStream_t s) {
   MfmaModel *f = m->mf;
-  PackSrc u{(const uint16_t *)unembed, nullptr, nullptr, m->d.vocab, 0, 0, 0, f->p_un.T, 0};
+  PackSrc u{(const uint16_t *)unembed, nullptr, nullptr, m->d.vocab, 0, 0, 0, f->p_un.T, 0, 0};
   int rc = pack(u, f->p_un, &f->un, s);
   if (rc) return rc;
   if (!f->un_part) f->un_part = (Top *)dalloc((size_t)f->p_un.n_slabs * 64 * sizeof(Top));
@@ -1005,7 +1056,7 @@ int mfma_set_head(la_model *m, const void *unembed, hipStream_t s) {
   return LA_OK;
 }
 
-static GemmDev dev_plan(const GemmPlan &p, int S) { return GemmDev{p.KT, p.T, p.n_slabs, S, p.N}; }
+static GemmDev dev_plan(const GemmPlan &p) { return GemmDev{p.KT, p.T, p.n_slabs, p.N}; }
 
 static size_t stack_lds_bytes(int MT) {
   // GEMM: tree buffers 3 MT T KB (the row-major tile reuses them) + row factors; the other
@@ -1053,6 +1104,29 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, hipStream_t
       default: rc = launch_stack_mt<4>(name, a, f->n_wgs, s); break;
     }
     if (rc) return rc;
+    if (f->trace && f->persistent) {  // debugging aid: per-phase timeline of workgroup 0 (100 MHz clock)
+      int np = a.p_end - a.p_begin;
+      std::vector<unsigned long long> h(3 * np);
+      LA_HIP(hipStreamSynchronize(s));
+      LA_HIP(hipMemcpy(h.data(), f->trace, h.size() * 8, hipMemcpyDeviceToHost));
+      fprintf(stderr, "[la trace] %s: %d phases, total %.1f us\n", name, np, (h[3 * np - 1] - h[0]) * 0.01);
+      std::vector<unsigned long long> w((size_t)2 * np * f->n_wgs);
+      LA_HIP(hipMemcpy(w.data(), f->trace + a.trace_wg_off, w.size() * 8, hipMemcpyDeviceToHost));
+      for (int q = 0; q < np && q < 1 + 2 * PHASES_PER_LAYER; ++q) {
+        fprintf(stderr, "[la trace]   phase %2d: barrier %6.2f us  work %7.2f us", q, (h[3 * q + 1] - h[3 * q]) * 0.01,
+                (h[3 * q + 2] - h[3 * q + 1]) * 0.01);
+        if (q > 0) {  // barrier q: spread of arrivals, and release latency after the last arrival
+          unsigned long long a0 = ~0ull, a1 = 0, r0 = ~0ull, r1 = 0;
+          for (int g = 0; g < f->n_wgs; ++g) {
+            unsigned long long ta = w[((size_t)q * f->n_wgs + g) * 2], trl = w[((size_t)q * f->n_wgs + g) * 2 + 1];
+            a0 = std::min(a0, ta); a1 = std::max(a1, ta); r0 = std::min(r0, trl); r1 = std::max(r1, trl);
+          }
+          fprintf(stderr, "   | arrivals spread %6.2f us, first release %5.2f us after last arrival, releases spread %5.2f us",
+                  (a1 - a0) * 0.01, ((double)r0 - (double)a1) * 0.01, (r1 - r0) * 0.01);
+        }
+        fprintf(stderr, "\n");
+      }
+    }
   }
   return LA_OK;
 }
@@ -1077,7 +1151,7 @@ static StackArgs base_stack_args(la_model *m, int Bp) {
   a.Hkv = d.n_kv_heads;
   a.dh = d.head_dim;
   a.F = d.d_ffn;
-  a.ncg = d.d_model / 32;
+  a.ncg = d.d_model / 16;
   a.eps = d.rms_eps;
   a.inv_d = 1.0f / (float)d.d_model;
   a.theta = (double)d.rope_theta;
@@ -1085,12 +1159,17 @@ static StackArgs base_stack_args(la_model *m, int Bp) {
   a.attn_a = f->attn_a;
   a.act_a = f->act_a;
   a.qf = f->qf;
-  a.part = f->part;
+  a.xa_stride = (size_t)LA_MAX_ROWS * d.d_model;
+  a.attn_stride = (size_t)LA_MAX_ROWS * m->qdim();
+  a.act_stride = (size_t)LA_MAX_ROWS * d.d_ffn;
+  a.rsq_stride = (size_t)LA_MAX_ROWS * (d.d_model / 16);
   a.rsq = f->rsq;
   a.o_part = f->o_part;
   a.ml_part = f->ml_part;
   a.cs = m->rope_cs;
   a.sync = f->sync;
+  a.trace = f->trace;
+  a.trace_wg_off = (size_t)3 * (2 + PHASES_PER_LAYER * d.n_layers);
   return a;
 }
 
@@ -1106,10 +1185,10 @@ int mfma_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32
   a.le = le;
   a.p_begin = 0;
   a.p_end = 1 + PHASES_PER_LAYER * (le - lb);
-  a.qkv = dev_plan(f->p_qkv, choose_split(f->p_qkv, f->n_wgs, a.MT, "LA_S_QKV"));
-  a.o = dev_plan(f->p_o, choose_split(f->p_o, f->n_wgs, a.MT, "LA_S_O"));
-  a.gu = dev_plan(f->p_gu, 1);
-  a.down = dev_plan(f->p_down, choose_split(f->p_down, f->n_wgs, a.MT, "LA_S_DOWN"));
+  a.qkv = dev_plan(f->p_qkv);
+  a.o = dev_plan(f->p_o);
+  a.gu = dev_plan(f->p_gu);
+  a.down = dev_plan(f->p_down);
   // key splits: a few blocks of 32 keys per workgroup, within the scratch sized at set-up
   int nkb = ceil_div(kv->L_bound + Bp, 32);
   a.ns = std::max(1, std::min(f->max_ns, ceil_div(nkb, env_int("LA_ATTN_KB", 2))));
@@ -1132,7 +1211,9 @@ int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, 
   a.mode = 1;
   a.p_begin = 0;
   a.p_end = 3;
-  a.un = dev_plan(f->p_un, 1);
+  a.un = dev_plan(f->p_un);
+  a.xa = f->xa_u;
+  a.rsq = f->rsq_u;
   a.x = const_cast<float *>(hidden);
   a.un_w = f->un;
   a.g_final = m->g_final;
