@@ -15,7 +15,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblookahead.so")
 
-SOURCES = ["la_api.hip", "la_generic.hip", "la_accept.hip", "la_mfma.hip"]
+SOURCES = ["la_api.hip", "la_generic.hip", "la_accept.hip", "la_mfma.hip",
+           "la_stack_mt1.hip", "la_stack_mt2.hip", "la_stack_mt3.hip", "la_stack_mt4.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -62,7 +63,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
         if verbose and bad:
             print("\n".join(bad[:20]))
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         list(ex.map(run, jobs))
     if force or jobs or _stale(LIB, objs):
         cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs

@@ -1,0 +1,1087 @@
+// bf16 MFMA path for gfx950: the whole layer stack of a verification step as ONE persistent
+// kernel, and a second launch of the same kernel for the unembedding with fused arg-max.
+//
+// A step reads every weight once (13 GB at the 30-layer Mistral-7B shape) and computes almost
+// nothing per byte, so it is bound by HBM.  The kernel is built so that the weight stream
+// never has to stop for the arithmetic that depends on it:
+//
+//   * One workgroup of 8 waves per CU stays resident for the whole launch.  Wave 7 is the
+//     PRODUCER: it walks this CU's share of the weights (one contiguous, pre-packed stream per
+//     CU, in the order the GEMMs will use it) and copies it HBM -> LDS with direct-to-LDS
+//     128-bit loads into a ring of 1 KB slots.  It knows nothing of phases or barriers: it
+//     runs ahead of the arithmetic by up to the size of the ring, across every grid barrier.
+//   * Waves 0..6 are CONSUMERS.  In a GEMM phase each takes every 7th k-tile of the CU's
+//     column tiles, reads the weight fragments from the ring (ds_read_b128), the activation
+//     fragments from L2, multiplies (MFMA 16x16x32 bf16, fp32 accumulate); the seven partial
+//     sums are added in a fixed tree through LDS and the epilogue of the GEMM runs on the
+//     finished tile.  The other phases (attention, operand preparation, arg-max) also run on
+//     the consumer waves.
+//   * Producer and consumers talk through monotonic counters in LDS (fragments landed; per
+//     consumer wave the first fragment it still needs).  The consumer waves synchronise among
+//     themselves with LDS counters too: the hardware workgroup barrier is not used after
+//     start-up, because the producer could not take part in it without stopping the stream.
+//   * Phases are separated by a grid barrier (relaxed device-scope atomics).  Everything one
+//     workgroup writes for another to read in a later phase is stored with the device-scope
+//     cache policy (sc1), so the barrier needs no cache flush or invalidate.
+//
+// Data layout
+//   weights      per CU c, per layer: [GEMM][pass][k-tile][tile-in-pass][lane][8] bf16.  Column
+//                tile t (16 columns) of a GEMM belongs to CU t mod G.  A fragment is the MFMA B
+//                operand of one k-tile (32 deep) x 16 columns: lane l holds column (l & 15),
+//                contraction indices 8 (l >> 4) .. +7; the direct-to-LDS load writes lane l's
+//                16 bytes at slot + 16 l, which is where the ds_read_b128 of lane l finds them.
+//   activations  [k-tile][row-tile][lane][8] bf16, the MFMA A operand, written by the epilogue
+//                that produces them, in buffers written once per launch (one per layer and
+//                use), so a reader can never find a stale copy in its L2.
+//   RMSNorm      is applied as ((x * g) W) * rsqrt(mean(x^2) + eps): the row factor after the
+//                contraction, from per-tile sums of squares the O / down epilogues emit.
+// All reductions have a fixed order: results are run-to-run identical, and a row's result
+// does not depend on how many rows the block has (except for the key split of attention).
+#pragma once
+#include "la_device.h"
+#include "la_internal.h"
+
+namespace la {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned u32x2;
+
+#define LDS_AS __attribute__((address_space(3)))
+typedef LDS_AS uint8_t *lds_t;
+
+constexpr int WG_THREADS = 512;
+constexpr int NCW = 7;                     // consumer waves 0..6; wave 7 streams the weights
+constexpr int CONS_THREADS = NCW * 64;
+constexpr int NSLOT = 128;                 // ring slots of 1 KB (a power of two)
+constexpr int CHUNK = 4;                   // fragments the producer issues back to back
+constexpr int FLIGHT = 12;                 // chunks in flight: 48 loads, the counter holds 63
+constexpr int RED_TILES = 8;               // 1 KB accumulator tiles per tree-reduction buffer
+constexpr int MAX_NT = 8;                  // column tiles of one pass
+constexpr int MAX_MT = LA_MAX_ROWS / 16;
+constexpr unsigned OOB = 0x80000000u;      // voffset beyond every buffer (all are < 2 GiB)
+constexpr unsigned RSRC_BYTES = 0x7fffffffu;
+constexpr int DEV = 16;                    // cache policy sc1: device-scope coherent load / store
+constexpr int NT_HINT = 2;                 // cache policy nt: streamed once
+constexpr int SYNC_GROUP = 16;             // workgroups per arrival counter of the grid barrier
+constexpr int SYNC_STRIDE = 64;            // 32-bit words between barrier variables (256 B)
+constexpr unsigned SPIN_LDS = 1u << 24;    // polls of an LDS word (~0.1 us each) before giving up
+constexpr unsigned SPIN_GLOBAL = 1u << 21; // polls of a global word (~1 us each) before giving up
+
+// LDS map (bytes)
+constexpr int LDS_RING = 0;
+constexpr int LDS_RED = NSLOT * 1024;                 // 3 buffers of RED_TILES KB; also the result tile
+constexpr int LDS_ML = LDS_RED + 3 * RED_TILES * 1024;  // attention: running max / sum per wave and lane
+constexpr int LDS_RS = LDS_ML + 4 * 512;              // [64] row factors of the norm
+constexpr int LDS_CTL = LDS_RS + 256;                 // control words
+constexpr int LDS_BYTES = LDS_CTL + 256;
+// control words
+constexpr int C_LANDED = 0;   // fragments of this workgroup's stream that have landed in the ring
+constexpr int C_DEAD = 1;     // a wait timed out: every wave leaves the kernel
+constexpr int C_CBAR = 2;     // arrivals at the consumer-wave barrier
+constexpr int C_GPASS = 3;    // last grid-barrier epoch seen released
+constexpr int C_PROG = 8;     // [8..14] per consumer wave: first stream fragment it still needs
+constexpr int C_TREE = 16;    // [16..22] per consumer wave: hand-off sequence number
+
+struct Top {  // running arg-max of one row: best value, its index, runner-up value
+  float v1;
+  int i1;
+  float v2;
+};
+
+__device__ __forceinline__ Top top_merge2(Top a, Top b) {
+  bool bw = (b.v1 > a.v1) || (b.v1 == a.v1 && b.i1 < a.i1);
+  Top r;
+  r.v1 = bw ? b.v1 : a.v1;
+  r.i1 = bw ? b.i1 : a.i1;
+  r.v2 = fmaxf(bw ? a.v1 : b.v1, fmaxf(a.v2, b.v2));
+  return r;
+}
+
+enum GemmMode { MODE_QKV = 0, MODE_RESID = 1, MODE_GATEUP = 2, MODE_UNEMBED = 3 };
+
+struct GemmDev {
+  int KT;      // k-tiles (32 deep)
+  int ntiles;  // 16-column tiles of the whole matrix
+  int ntp;     // tiles per pass
+};
+
+struct LayerGains {
+  const float *g_attn, *g_mlp;
+};
+
+struct StackArgs {
+  const LayerGains *gains;
+  int mode;  // 0: layer stack, 1: unembedding
+  int lb, le;
+  int Bp, MT, d, Hq, Hkv, dh, F, ncg;
+  float eps, inv_d;
+  double theta;
+  GemmDev qkv, o, gu, down, un;
+  // weight stream: CU c reads wstream + c * cu_bytes; per layer seg_frags fragments apart
+  const uint8_t *wstream;
+  size_t cu_bytes;
+  unsigned seg_frags;
+  float *x;
+  const int32_t *pos;
+  const uint64_t *vis;
+  // write-once operand / statistics buffers, indexed by absolute layer
+  uint16_t *xa, *attn_a, *act_a, *qf;
+  size_t xa_stride, attn_stride, act_stride, rsq_stride;  // elements per (layer, use)
+  float *rsq, *cs;
+  uint16_t *K, *V;
+  size_t layer_elems;
+  const int32_t *L_dev;
+  int max_len;
+  int32_t *err;
+  const float *g_final;
+  Top *un_part;
+  int un_parts_per_cu;
+  int32_t *ids;
+  float *top2;
+  unsigned *sync;
+  unsigned epoch0, n_groups;
+  unsigned long long *trace;  // optional: per phase 4 timestamps of workgroup 0, then per workgroup producer statistics
+  int trace_phases;
+};
+
+// Values that are the same in every lane, moved to scalar registers.  The compiler cannot see
+// that words read from LDS or memory are wave-uniform; without this it guards loads with
+// per-lane loops and keeps loop control in vector registers.
+__device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T *uni_ptr(T *p) {
+  uint64_t u = (uint64_t)p;
+  uint32_t lo = uni((unsigned)u), hi = uni((unsigned)(u >> 32));
+  return (T *)(((uint64_t)hi << 32) | lo);
+}
+
+// ---- LDS control words: inline assembly, so that the compiler neither caches them nor puts
+// waits for the producer's outstanding direct-to-LDS loads in front of them --------------------
+__device__ __forceinline__ unsigned ctl_read(unsigned addr) {
+  unsigned v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+  return uni(v);
+}
+__device__ __forceinline__ unsigned ctl_read_lanes(unsigned addr) {  // a different word per lane
+  unsigned v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void ctl_write(unsigned addr, unsigned v) {
+  asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void ctl_add(unsigned addr, unsigned v) {
+  asm volatile("ds_add_u32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // at most N vector-memory operations outstanding
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+struct Wave {          // per-wave view of the workgroup's LDS and sequence numbers
+  unsigned ctl;        // LDS byte address of the control words
+  int w, lane;
+  unsigned cbar_seq;   // consumer barrier: arrivals expected so far
+  unsigned tree_seq;   // hand-off sequence
+  unsigned seen;       // cached copy of C_LANDED
+  int trace_phase;
+  unsigned long long wait_ticks;  // tracing: time spent waiting for weights to land
+  bool dead;
+};
+
+// Spin until the control word reaches `want`.  Returns false (and raises C_DEAD) on a timeout
+// or when another wave has raised C_DEAD.
+__device__ __forceinline__ bool ctl_wait_ge(Wave &wv, int word, unsigned want) {
+  unsigned spins = 0;
+  for (;;) {
+    unsigned v = ctl_read(wv.ctl + 4 * word);
+    if ((int)(v - want) >= 0) return true;
+    __builtin_amdgcn_s_sleep(1);
+    ++spins;
+    if ((spins & 255u) == 0) {
+      if (ctl_read(wv.ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS) {
+        ctl_write(wv.ctl + 4 * C_DEAD, 1u);
+        wv.dead = true;
+        return false;
+      }
+    }
+  }
+}
+
+// Barrier of the seven consumer waves.  LDS executes one wave's operations in order, so the
+// data a wave wrote before arriving is visible to every wave that has seen the arrival.
+__device__ __forceinline__ bool cons_barrier(Wave &wv) {
+  wv.cbar_seq += NCW;
+  if (wv.lane == 0) ctl_add(wv.ctl + 4 * C_CBAR, 1u);
+  return ctl_wait_ge(wv, C_CBAR, wv.cbar_seq);
+}
+
+// ---- device-scope accessors ------------------------------------------------------------------
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const void *p) {
+  return __builtin_amdgcn_make_buffer_rsrc(uni_ptr(const_cast<void *>(p)), 0, RSRC_BYTES, 0x00020000);
+}
+__device__ __forceinline__ u32x4 ld128(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, DEV);
+}
+__device__ __forceinline__ void st128(__amdgpu_buffer_rsrc_t r, unsigned byte_off, u32x4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(v, r, byte_off, 0, DEV);
+}
+__device__ __forceinline__ void st64(__amdgpu_buffer_rsrc_t r, unsigned byte_off, u32x2 v) {
+  __builtin_amdgcn_raw_buffer_store_b64(v, r, byte_off, 0, DEV);
+}
+__device__ __forceinline__ float ld32f(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, DEV));
+}
+__device__ __forceinline__ void st32f(__amdgpu_buffer_rsrc_t r, unsigned byte_off, float v) {
+  __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), r, byte_off, 0, DEV);
+}
+__device__ __forceinline__ void st16(__amdgpu_buffer_rsrc_t r, unsigned byte_off, uint16_t v) {
+  __builtin_amdgcn_raw_buffer_store_b16(v, r, byte_off, 0, DEV);
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+}
+// byte offset of the 16-byte piece (row b, columns col..col+7, col a multiple of 8) of an
+// operand-fragment buffer with MT row tiles
+__device__ __forceinline__ unsigned frag_piece(int col, int b, int MT) {
+  return (unsigned)((((size_t)(col >> 5) * MT + (b >> 4)) * 64 + (b & 15) + 16 * ((col & 31) >> 3)) * 16);
+}
+
+__device__ __forceinline__ void trace_mark(const StackArgs &a, const Wave &wv, int phase, int k) {
+  if (a.trace && blockIdx.x == 0 && wv.w == 0 && wv.lane == 0 && phase < a.trace_phases) a.trace[4 * phase + k] = wall_clock64();
+}
+
+// tiles of a matrix that belong to this CU (tile t -> CU t mod G)
+__device__ __forceinline__ int my_tiles(int ntiles) {
+  int c = blockIdx.x, G = gridDim.x;
+  return ntiles > c ? (ntiles - c + G - 1) / G : 0;
+}
+
+// ---- grid barrier (consumer waves) -----------------------------------------------------------
+// Arrival counters per group of SYNC_GROUP workgroups, one top counter, one release word; all
+// monotonic (epoch e is complete when a counter reaches e * members).  Only relaxed device-scope
+// atomics: the data exchanged between workgroups travels with sc1 accesses, and each wave waits
+// for its own stores before the workgroup arrives.  Every spin is bounded: on a timeout the
+// error flag is raised and the workgroup leaves the kernel (the others then time out too).
+__device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned epoch) {
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  wait_vmcnt<0>();  // this wave's stores are acknowledged
+  if (!cons_barrier(wv)) return false;
+  if (wv.w == 0) {
+    if (wv.lane == 0) {
+      unsigned n = gridDim.x;
+      unsigned g = blockIdx.x / SYNC_GROUP;
+      unsigned gsize = (g + 1) * SYNC_GROUP <= n ? SYNC_GROUP : n - g * SYNC_GROUP;
+      unsigned *gc = a.sync + SYNC_STRIDE * g, *top = a.sync + SYNC_STRIDE * 64, *rel = a.sync + SYNC_STRIDE * 65;
+      unsigned old = __hip_atomic_fetch_add(gc, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old + 1 == epoch * gsize) {
+        unsigned t = __hip_atomic_fetch_add(top, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (t + 1 == epoch * a.n_groups) __hip_atomic_store(rel, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      unsigned spins = 0;
+      bool ok = true;
+      while ((int)(__hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        if (++spins > SPIN_GLOBAL) {
+          __hip_atomic_fetch_or(a.err, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          ok = false;
+          break;
+        }
+      }
+      if (ok) ctl_write(wv.ctl + 4 * C_GPASS, epoch);
+      else ctl_write(wv.ctl + 4 * C_DEAD, 1u);
+    }
+  }
+  return ctl_wait_ge(wv, C_GPASS, epoch);
+}
+
+// ---- producer ----------------------------------------------------------------------------------
+// Streams n_seg segments of seg_used fragments each (a layer's share of this CU, padded to whole
+// chunks; seg_stride fragments apart in memory) into the ring, in order.  Keeps FLIGHT chunks in flight, publishes
+// C_LANDED as chunks land, and never overwrites a slot before every consumer wave has moved
+// past the fragment it held.
+__device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_AS uint8_t *ring, unsigned first_seg, unsigned n_seg,
+                                         unsigned seg_used, unsigned seg_stride, unsigned long long *stats) {
+  const int lane = threadIdx.x & 63;
+  const uint8_t *base = uni_ptr(a.wstream + (size_t)blockIdx.x * a.cu_bytes);
+  __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base), 0, uni((unsigned)a.cu_bytes), 0x00020000);
+  first_seg = uni(first_seg);
+  n_seg = uni(n_seg);
+  seg_used = uni(seg_used);
+  seg_stride = uni(seg_stride);
+  ctl = uni(ctl);
+  const unsigned total = n_seg * seg_used;
+  unsigned next = 0, landed = 0, inflight = 0, free_until = NSLOT;
+  unsigned seg_off = first_seg * seg_stride, f_in_seg = 0;  // memory position of fragment `next`
+  unsigned polls = 0, full_events = 0;
+  unsigned long long t_drain = 0, t_poll = 0, t_flight = 0;
+  const bool tr = stats != nullptr;
+  const unsigned long long t_begin = tr ? wall_clock64() : 0ull;
+  while (next < total) {
+    if (next + CHUNK > free_until) {
+      // ring full: publish everything in flight, then poll the consumers
+      unsigned long long t0 = tr ? wall_clock64() : 0ull;
+      if (inflight) {
+        wait_vmcnt<0>();
+        landed = next < total ? next : total;
+        ctl_write(ctl + 4 * C_LANDED, landed);
+        inflight = 0;
+      }
+      ++full_events;
+      unsigned long long t1 = tr ? wall_clock64() : 0ull;
+      t_drain += t1 - t0;
+      unsigned spins = 0;
+      for (;;) {
+        unsigned c = ctl_read_lanes(ctl + 4 * (C_PROG + (lane < NCW ? lane : 0)));
+#pragma unroll
+        for (int o = 1; o < 8; o <<= 1) c = min(c, (unsigned)__shfl_xor((int)c, o, 64));
+        c = __builtin_amdgcn_readfirstlane(c);
+        free_until = c + NSLOT;
+        if (next + CHUNK <= free_until) break;
+        __builtin_amdgcn_s_sleep(1);
+        ++polls;
+        if ((++spins & 255u) == 0 && (ctl_read(ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS)) {
+          ctl_write(ctl + 4 * C_DEAD, 1u);
+          return;
+        }
+      }
+      if (tr) t_poll += wall_clock64() - t1;
+    }
+    {
+      // a chunk is contiguous in memory and in the ring (segments are padded to whole chunks):
+      // one scalar offset, one LDS base, the instruction offset steps through both
+      LDS_AS void *dst = (LDS_AS void *)(ring + (next & (NSLOT - 1)) * 1024);
+      const unsigned soff = (seg_off + f_in_seg) * 1024u;
+      const unsigned vo = (unsigned)lane * 16u;
+      static_assert(CHUNK == 4, "the chunk is unrolled by hand");
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 0, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 1024, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 2048, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 3072, NT_HINT);
+      f_in_seg += CHUNK;
+      if (f_in_seg == seg_used) {
+        f_in_seg = 0;
+        seg_off += seg_stride;
+      }
+    }
+    next += CHUNK;
+    if (++inflight == FLIGHT) {
+      unsigned long long t0 = tr ? wall_clock64() : 0ull;
+      wait_vmcnt<(FLIGHT - 1) * CHUNK>();
+      if (tr) t_flight += wall_clock64() - t0;
+      landed += CHUNK;
+      ctl_write(ctl + 4 * C_LANDED, landed);
+      --inflight;
+    }
+  }
+  wait_vmcnt<0>();
+  ctl_write(ctl + 4 * C_LANDED, total);
+  if (stats && lane == 0) {
+    stats[0] = polls;
+    stats[1] = full_events;
+    stats[2] = t_drain;
+    stats[3] = t_poll;
+    stats[4] = t_flight;
+    stats[5] = wall_clock64() - t_begin;
+  }
+}
+
+// ---- GEMM pass (consumer waves) --------------------------------------------------------------
+template <int MT, int NT>
+struct Depth {  // k-tiles of the activation operand in flight per wave
+  static constexpr int raw = (176 - 4 * MT * NT - 4 * NT) / (4 * MT);
+  static constexpr int value = raw < 2 ? 2 : (raw > 6 ? 6 : raw);
+};
+
+struct GemmIo {
+  const uint16_t *A;      // operand fragments (a write-once buffer: loaded through the cache)
+  int mode;
+  const float *rsq_in;    // MODE_QKV, MODE_GATEUP: sums of squares of the input rows [64][ncg]
+  uint16_t *Kc, *Vc;      // MODE_QKV: this layer's cache
+  int L;
+  const float *gain;      // MODE_RESID: gain of the next norm (nullptr: no fragments wanted)
+  uint16_t *xa_out;       // MODE_RESID: fragments of x * gain for the next GEMM
+  float *rsq_out;         // MODE_RESID: sums of squares of the new x
+  uint16_t *act_a;        // MODE_GATEUP: fragments for the down projection
+  Top *un_part;           // MODE_UNEMBED
+  int part0;              // MODE_UNEMBED: index of this pass's first partial record
+};
+
+// Row factors rsqrt(mean(x^2) + eps) of the block's rows into LDS: wave w takes rows w, w+7, ...
+// Loads first, fixed-order reduction after: the caller puts the k-loop in between.
+template <int MT>
+struct RowStat {
+  static constexpr int NR = (16 * MT + NCW - 1) / NCW;
+  f32x4 v[NR];
+};
+template <int MT>
+__device__ __forceinline__ void rowstat_load(const StackArgs &a, const Wave &wv, const float *rsq_in, RowStat<MT> &rs) {
+  // ncg / 4 vectors per row; rows are short (ncg <= 1024): lanes beyond the row read nothing
+#pragma unroll
+  for (int i = 0; i < RowStat<MT>::NR; ++i) {
+    int row = wv.w + NCW * i;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (row < a.Bp)
+      for (int c4 = wv.lane; c4 < a.ncg / 4; c4 += 64) {
+        f32x4 t = *reinterpret_cast<const f32x4 *>(rsq_in + (size_t)row * a.ncg + 4 * c4);
+        s += t;
+      }
+    rs.v[i] = s;
+  }
+}
+template <int MT>
+__device__ __forceinline__ void rowstat_finish(const StackArgs &a, const Wave &wv, const RowStat<MT> &rs, LDS_AS float *rs_lds) {
+#pragma unroll
+  for (int i = 0; i < RowStat<MT>::NR; ++i) {
+    int row = wv.w + NCW * i;
+    float s = (rs.v[i][0] + rs.v[i][1]) + (rs.v[i][2] + rs.v[i][3]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (row < 16 * MT && wv.lane == 0) rs_lds[row] = row < a.Bp ? 1.0f / sqrtf(s * a.inv_d + a.eps) : 0.f;
+  }
+}
+
+// One pass: NT column tiles of this CU (local tiles tile0 .. tile0+NT-1), the whole contraction.
+// sbase = index in the workgroup's stream of the pass's first fragment.
+template <int MT, int NT>
+__device__ __forceinline__ bool gemm_pass(const StackArgs &a, Wave &wv, lds_t lds, const GemmIo &io, int KT, unsigned sbase,
+                                          int tile0, bool need_rs) {
+  constexpr int DA = Depth<MT, NT>::value;
+  constexpr int TPC = (RED_TILES / MT) < NT ? (RED_TILES / MT) : NT;  // column tiles per reduction chunk
+  constexpr int LDT = 16 * TPC + 4;                                  // padded row length of the result tile
+  const int w = uni(wv.w), lane = wv.lane;
+  KT = uni(KT);
+  sbase = uni(sbase);
+  tile0 = uni(tile0);
+  LDS_AS const u32x4 *ring = (LDS_AS const u32x4 *)(lds + LDS_RING);
+  LDS_AS f32x4 *red = (LDS_AS f32x4 *)(lds + LDS_RED);
+  LDS_AS float *tile = (LDS_AS float *)(lds + LDS_RED);
+  LDS_AS float *rs_lds = (LDS_AS float *)(lds + LDS_RS);
+  __amdgpu_buffer_rsrc_t ra = rsrc_of(io.A);
+  const unsigned voff = lane * 16;
+  const int nk = KT > w ? (KT - w + NCW - 1) / NCW : 0;  // this wave's k-tiles: w, w + 7, ...
+
+  u32x4 rA[DA][MT];
+  auto load_a = [&](int slot, int i) {
+    unsigned vo = (i < nk) ? voff : OOB;  // out of range: zeros come back, no memory traffic
+    unsigned kt = (unsigned)(w + NCW * i);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) rA[slot][mt] = __builtin_amdgcn_raw_buffer_load_b128(ra, vo, (kt * MT + mt) * 1024u, 0);
+  };
+#pragma unroll
+  for (int s = 0; s < DA; ++s) load_a(s, s);
+  RowStat<MT> rs;
+  if (need_rs) rowstat_load(a, wv, io.rsq_in, rs);
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int i0 = 0; i0 < nk; i0 += DA) {
+#pragma unroll
+    for (int s = 0; s < DA; ++s) {
+      const int i = i0 + s;
+      if (i < nk) {
+        const unsigned kt = (unsigned)(w + NCW * i);
+        const unsigned first = sbase + kt * NT;
+        if ((int)(wv.seen - (first + NT)) < 0) {
+          unsigned spins = 0;
+          const unsigned long long t0 = a.trace ? wall_clock64() : 0ull;
+          for (;;) {
+            wv.seen = ctl_read(wv.ctl + 4 * C_LANDED);
+            if ((int)(wv.seen - (first + NT)) >= 0) break;
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 255u) == 0 && (ctl_read(wv.ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS)) {
+              ctl_write(wv.ctl + 4 * C_DEAD, 1u);
+              wv.dead = true;
+              return false;
+            }
+          }
+          if (a.trace) wv.wait_ticks += wall_clock64() - t0;
+        }
+        u32x4 rW[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) rW[t] = ring[((first + t) & (NSLOT - 1)) * 64 + lane];
+        // the reads above are in the LDS queue before this write: when the producer sees the
+        // new value, the slots have been read
+        {
+          unsigned nxt = kt + NCW < (unsigned)KT ? kt + NCW : (unsigned)KT;
+          if (lane == 0) ctl_write(wv.ctl + 4 * (C_PROG + w), sbase + nxt * NT);
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int t = 0; t < NT; ++t)
+            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rA[s][mt]),
+                                                                  __builtin_bit_cast(bf16x8, rW[t]), acc[mt][t], 0, 0, 0);
+        load_a(s, i + DA);
+      }
+    }
+  }
+  // nothing of this pass is needed any more (also covers a wave that had no k-tile)
+  if (lane == 0) ctl_write(wv.ctl + 4 * (C_PROG + w), sbase + (unsigned)KT * NT);
+  if (need_rs) rowstat_finish(a, wv, rs, rs_lds);
+  if (a.trace && blockIdx.x == 0 && w == 0 && lane == 0 && tile0 == 0 && wv.trace_phase < a.trace_phases) {
+    a.trace[4 * wv.trace_phase + 1] = wall_clock64();
+    a.trace[4 * wv.trace_phase + 3] = wv.wait_ticks;
+    wv.wait_ticks = 0;
+  }
+
+  // ---- reduction over the seven waves and epilogue, TPC column tiles at a time ----
+#pragma unroll
+  for (int c0 = 0; c0 < NT; c0 += TPC) {
+    auto put = [&](int buf) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int tt = 0; tt < TPC; ++tt)
+          if (c0 + tt < NT) red[(buf * RED_TILES + mt * TPC + tt) * 64 + lane] = acc[mt][c0 + tt];
+    };
+    auto add = [&](int buf) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int tt = 0; tt < TPC; ++tt)
+          if (c0 + tt < NT) acc[mt][c0 + tt] += red[(buf * RED_TILES + mt * TPC + tt) * 64 + lane];
+    };
+    const unsigned q = wv.tree_seq;
+    auto signal = [&](unsigned v) {
+      if (lane == 0) ctl_write(wv.ctl + 4 * (C_TREE + w), v);
+    };
+    // ((w0 + w4) + (w2 + w6)) + (w3 + (w1 + w5)); a wave only ever overwrites a buffer it has
+    // itself finished reading
+    if (w >= 4) { put(w - 4); signal(q + 1); }
+    if (w < 3) { if (!ctl_wait_ge(wv, C_TREE + w + 4, q + 1)) return false; add(w); }
+    if (w == 2) { put(2); signal(q + 2); }
+    if (w == 1) { put(1); signal(q + 2); }
+    if (w == 0) { if (!ctl_wait_ge(wv, C_TREE + 2, q + 2)) return false; add(2); }
+    if (w == 3) { if (!ctl_wait_ge(wv, C_TREE + 1, q + 2)) return false; add(1); put(1); signal(q + 3); }
+    if (w == 0) {
+      if (!ctl_wait_ge(wv, C_TREE + 3, q + 3)) return false;
+      add(1);
+      // finished tile, row-major: acc[mt][t][i] is (row 16 mt + 4 (lane >> 4) + i, column 16 t + (lane & 15))
+      const int q4 = lane >> 4, c16 = lane & 15;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int tt = 0; tt < TPC; ++tt)
+          if (c0 + tt < NT)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) tile[(16 * mt + 4 * q4 + i) * LDT + 16 * tt + c16] = acc[mt][c0 + tt][i];
+      signal(q + 4);
+    }
+    wv.tree_seq = q + 4;
+    if (!ctl_wait_ge(wv, C_TREE + 0, q + 4)) return false;
+    __atomic_signal_fence(__ATOMIC_SEQ_CST);
+
+    const int tid = w * 64 + lane;
+    const int ntc = (NT - c0) < TPC ? (NT - c0) : TPC;  // column tiles in this chunk
+    const int G = gridDim.x, cu = blockIdx.x;
+    if (io.mode == MODE_QKV) {
+      // A tile holds channels 8j..8j+7 (columns 0..7) and dh/2 + 8j.. (columns 8..15) of one
+      // head: both members of eight RoPE pairs.  One thread per (row, tile).
+      for (int it = tid; it < a.Bp * ntc; it += CONS_THREADS) {
+        const int b = it / ntc, tt = it - b * ntc;
+        const int gt = cu + G * (tile0 + c0 + tt);
+        const int half = a.dh >> 1, spj = a.dh >> 4, grp = a.Hq / a.Hkv;
+        const int hs = gt / spj, j = gt - hs * spj;
+        const float rsf = rs_lds[b];
+        LDS_AS const float *tr = tile + b * LDT + 16 * tt;
+        const float qscale = hs < a.Hq ? 1.0f / sqrtf((float)a.dh) : 1.0f;
+        float y0[8], y1[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          float x0 = tr[k] * rsf, x1 = tr[8 + k] * rsf;
+          if (hs < a.Hq + a.Hkv) {
+            float c = a.cs[((size_t)b * half + 8 * j + k) * 2], sn = a.cs[((size_t)b * half + 8 * j + k) * 2 + 1];
+            y0[k] = (x0 * c - x1 * sn) * qscale;
+            y1[k] = (x1 * c + x0 * sn) * qscale;
+          } else {
+            y0[k] = x0;
+            y1[k] = x1;
+          }
+        }
+        u32x4 lo = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y0[4], y0[5]), pack_bf16(y0[6], y0[7])};
+        u32x4 hi = {pack_bf16(y1[0], y1[1]), pack_bf16(y1[2], y1[3]), pack_bf16(y1[4], y1[5]), pack_bf16(y1[6], y1[7])};
+        const int o_lo = j, o_hi = (half >> 3) + j;  // channel octets of the two pieces
+        if (hs < a.Hq) {
+          __amdgpu_buffer_rsrc_t rqf = rsrc_of(a.qf);
+          int kvh = hs / grp, jq = hs - kvh * grp, rt = jq * MT + (b >> 4);
+          size_t fb = ((size_t)kvh * (grp * MT) + rt) * (a.dh >> 5);
+          st128(rqf, (unsigned)(((fb + (o_lo >> 2)) * 64 + (b & 15) + 16 * (o_lo & 3)) * 16), lo);
+          st128(rqf, (unsigned)(((fb + (o_hi >> 2)) * 64 + (b & 15) + 16 * (o_hi & 3)) * 16), hi);
+        } else if (hs < a.Hq + a.Hkv) {
+          __amdgpu_buffer_rsrc_t rk = rsrc_of(io.Kc);
+          size_t rb = ((size_t)(io.L + b) * a.Hkv + (hs - a.Hq)) * a.dh;
+          st128(rk, (unsigned)((rb + 8 * o_lo) * 2), lo);
+          st128(rk, (unsigned)((rb + 8 * o_hi) * 2), hi);
+        } else {
+          __amdgpu_buffer_rsrc_t rv = rsrc_of(io.Vc);
+          int h = hs - a.Hq - a.Hkv;
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            st16(rv, (unsigned)(v_index(true, io.L + b, h, 8 * j + k, a.Hkv, a.dh) * 2), float_to_bf16(y0[k]));
+            st16(rv, (unsigned)(v_index(true, io.L + b, h, half + 8 * j + k, a.Hkv, a.dh) * 2), float_to_bf16(y1[k]));
+          }
+        }
+      }
+    } else if (io.mode == MODE_RESID) {
+      // x[:, tile columns] += tile; sum of squares of the new values; fragments of x * gain.
+      // Two threads per (row, tile), eight columns each.  This workgroup owns these columns of
+      // x in every layer, so x needs no device-scope accesses.
+      for (int it = tid; it < a.Bp * ntc * 2; it += CONS_THREADS) {
+        const int oct = it & 1, bt = it >> 1;
+        const int b = bt / ntc, tt = bt - b * ntc;
+        const int gt = cu + G * (tile0 + c0 + tt);
+        const int col = 16 * gt + 8 * oct;
+        f32x4 *xp = reinterpret_cast<f32x4 *>(a.x + (size_t)b * a.d + col);
+        LDS_AS const float *tr = tile + b * LDT + 16 * tt + 8 * oct;
+        f32x4 x0 = xp[0], x1 = xp[1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          x0[i] += tr[i];
+          x1[i] += tr[4 + i];
+        }
+        xp[0] = x0;
+        xp[1] = x1;
+        float sq = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
+        sq += __shfl_xor(sq, 1, 64);
+        if (io.gain) {
+          if (oct == 0) st32f(rsrc_of(io.rsq_out), (unsigned)(b * a.ncg + gt) * 4, sq);
+          const float *gp = io.gain + col;
+          u32x4 v = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
+                     pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+          st128(rsrc_of(io.xa_out), frag_piece(col, b, MT), v);
+        }
+      }
+    } else if (io.mode == MODE_GATEUP) {
+      // tile columns: 8 gate channels, then the same 8 channels of up
+      __amdgpu_buffer_rsrc_t rp = rsrc_of(io.act_a);
+      for (int it = tid; it < a.Bp * ntc; it += CONS_THREADS) {
+        const int b = it / ntc, tt = it - b * ntc;
+        const int gt = cu + G * (tile0 + c0 + tt);
+        const float rsf = rs_lds[b];
+        LDS_AS const float *gp = tile + b * LDT + 16 * tt, *up = gp + 8;
+        float act[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float g = gp[i] * rsf, u = up[i] * rsf;
+          act[i] = g / (1.0f + __expf(-g)) * u;
+        }
+        st128(rp, frag_piece(8 * gt, b, MT),
+              u32x4{pack_bf16(act[0], act[1]), pack_bf16(act[2], act[3]), pack_bf16(act[4], act[5]), pack_bf16(act[6], act[7])});
+      }
+    } else {  // MODE_UNEMBED: arg-max of each row over this chunk's columns, 4 threads per row
+      const int row = tid >> 2, j = tid & 3;
+      Top best{-INFINITY, 0x7fffffff, -INFINITY};
+      if (row < a.Bp)
+        for (int c = j; c < 16 * ntc; c += 4) {
+          int gt = cu + G * (tile0 + c0 + (c >> 4));
+          best = top_merge2(best, Top{tile[row * LDT + c], 16 * gt + (c & 15), -INFINITY});
+        }
+#pragma unroll
+      for (int o = 1; o < 4; o <<= 1) {
+        Top other;
+        other.v1 = __shfl_xor(best.v1, o, 64);
+        other.i1 = __shfl_xor(best.i1, o, 64);
+        other.v2 = __shfl_xor(best.v2, o, 64);
+        best = top_merge2(best, other);
+      }
+      if (j == 0 && row < a.Bp) {
+        __amdgpu_buffer_rsrc_t rp = rsrc_of(io.un_part);
+        unsigned o = (unsigned)(((size_t)(io.part0 + c0 / TPC) * 64 + row) * sizeof(Top));
+        st32f(rp, o, best.v1);
+        __builtin_amdgcn_raw_buffer_store_b32((unsigned)best.i1, rp, o + 4, 0, DEV);
+        st32f(rp, o + 8, best.v2);
+      }
+    }
+    // everyone has finished reading the tile before the buffers are written again
+    if (!cons_barrier(wv)) return false;
+  }
+  return true;
+}
+
+// All passes of one GEMM for this CU.  sbase: stream index of the GEMM's first fragment.
+// Returns the number of fragments the GEMM occupies in this CU's stream through *used.
+template <int MT>
+__device__ __forceinline__ bool gemm_phase(const StackArgs &a, Wave &wv, lds_t lds, GemmIo io, const GemmDev &g, unsigned sbase,
+                                           bool need_rs) {
+  const int nt = uni(my_tiles(g.ntiles));
+  sbase = uni(sbase);
+  int part = 0;
+  for (int t0 = 0; t0 < nt; t0 += g.ntp) {
+    const int n = nt - t0 < g.ntp ? nt - t0 : g.ntp;
+    io.part0 = part;
+    bool ok;
+    switch (n) {
+      case 1: ok = gemm_pass<MT, 1>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 2: ok = gemm_pass<MT, 2>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 3: ok = gemm_pass<MT, 3>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 4: ok = gemm_pass<MT, 4>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 5: ok = gemm_pass<MT, 5>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 6: ok = gemm_pass<MT, 6>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 7: ok = gemm_pass<MT, 7>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      default: ok = gemm_pass<MT, 8>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+    }
+    if (!ok) return false;
+    sbase += (unsigned)(n * g.KT);
+    constexpr int tpc_max = RED_TILES / MT;
+    part += (n + tpc_max - 1) / tpc_max;
+  }
+  return true;
+}
+
+// ---- first operand of a launch: norm statistics and fragments of x * gain ----------------------
+// One thread per (row, 8 columns).  Sums of squares are kept per 16 columns, the granularity of
+// the GEMM epilogues that produce them in later phases.
+__device__ __forceinline__ void prep_phase(const StackArgs &a, const Wave &wv, const float *gain, uint16_t *xa_out, float *rsq_out) {
+  __amdgpu_buffer_rsrc_t rq = rsrc_of(rsq_out), rx = rsrc_of(xa_out);
+  const int octs = a.d >> 3, total = a.Bp * octs;
+  for (int it = blockIdx.x * CONS_THREADS + wv.w * 64 + wv.lane; it < total; it += gridDim.x * CONS_THREADS) {
+    const int r = it / octs, oct = it - r * octs, c0 = oct * 8;
+    const f32x4 *xp = reinterpret_cast<const f32x4 *>(a.x + (size_t)r * a.d + c0);
+    f32x4 x0 = xp[0], x1 = xp[1];
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
+    sq += __shfl_xor(sq, 1, 64);  // octs is even: both octets of a 16-column group sit in one wave
+    if ((oct & 1) == 0) st32f(rq, (unsigned)(r * a.ncg + (oct >> 1)) * 4, sq);
+    const float *gp = gain + c0;
+    u32x4 v = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
+               pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+    st128(rx, frag_piece(c0, r, a.MT), v);
+  }
+}
+
+// cos/sin of pos[b] * theta^(-2i/dh) in double (exact to float rounding at any cache position)
+__device__ __forceinline__ void rope_table_phase(const StackArgs &a, const Wave &wv) {
+  __amdgpu_buffer_rsrc_t rc = rsrc_of(a.cs);
+  int half = a.dh >> 1, total = a.Bp * half;
+  for (int e = blockIdx.x * CONS_THREADS + wv.w * 64 + wv.lane; e < total; e += gridDim.x * CONS_THREADS) {
+    int b = e / half, i = e - b * half;
+    double inv = exp2(-(double)i / (double)half * log2(a.theta));
+    double s, c;
+    sincos((double)a.pos[b] * inv, &s, &c);
+    st32f(rc, (unsigned)e * 8, (float)c);
+    st32f(rc, (unsigned)e * 8 + 4, (float)s);
+  }
+}
+
+// ---- masked-block GQA attention ------------------------------------------------------------------
+// Unit = (kv head, tile of 16 q-rows of the head's group); one workgroup per unit.  The seven
+// consumer waves split the key blocks (of 32 keys) round-robin, each keeps a running max / sum
+// and an unnormalised output, and the seven are merged in the same fixed tree as the GEMMs.
+// Scores are computed transposed (keys x q-rows) so that the probabilities leave the MFMA in the
+// operand layout of the second product:
+//   S^T = K Q^T      A = K tile [16 keys x 32 dh],   B = q fragment        -> lane: 4 keys of one q-row
+//   O^T = V^T P^T    A = V^T tile [16 dh x 32 keys], B = p of 2 key tiles  -> lane: 4 channels of one q-row
+// V is stored key-blocked (v_index) so that the V^T tile is one 128-bit load per lane.
+template <int DH>
+__device__ __forceinline__ bool attention_phase(const StackArgs &a, Wave &wv, lds_t lds, const uint16_t *Kc, const uint16_t *Vc,
+                                                uint16_t *attn_out, int L) {
+  constexpr int KT = DH / 32, DT = DH / 16;
+  static_assert(DT <= RED_TILES, "one wave's output must fit a reduction buffer");
+  __amdgpu_buffer_rsrc_t rk = rsrc_of(Kc), rv = rsrc_of(Vc), rqf = rsrc_of(a.qf), ra = rsrc_of(attn_out);
+  LDS_AS f32x4 *red = (LDS_AS f32x4 *)(lds + LDS_RED);
+  LDS_AS float *mlb = (LDS_AS float *)(lds + LDS_ML);
+  const int w = uni(wv.w), lane = wv.lane, q4 = lane >> 4, c16 = lane & 15;
+  const int g = a.Hq / a.Hkv, n_rt = g * a.MT;
+  const int total = L + a.Bp, nkb = (total + 31) >> 5;
+  for (int u = blockIdx.x; u < a.Hkv * n_rt; u += gridDim.x) {
+    const int kvh = u / n_rt, rt = u - kvh * n_rt;
+    const int b = (rt % a.MT) * 16 + c16;  // block row of this lane's q-row
+    const uint64_t vb = b < a.Bp ? a.vis[b] : 0ull;
+    bf16x8 q[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+      q[kt] = __builtin_bit_cast(bf16x8, ld128(rqf, (unsigned)(((((size_t)kvh * n_rt + rt) * KT + kt) * 64 + lane) * 16)));
+    f32x4 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -1e30f, l_run = 0.f;
+    u32x4 ka[KT], kbv[KT], vt[DT], nka[KT], nkbv[KT], nvt[DT];
+    auto load_kv = [&](int kb, u32x4 *pa, u32x4 *pb, u32x4 *pv) {
+      const unsigned k_off = kb < nkb ? (unsigned)((((size_t)(kb * 32 + c16) * a.Hkv + kvh) * DH + 8 * q4) * 2) : OOB;
+      const unsigned v_off = kb < nkb ? (unsigned)(((((size_t)kb * a.Hkv + kvh) * DH + c16) * 32 + 8 * q4) * 2) : OOB;
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+        pa[kt] = ld128(rk, k_off + kt * 64);
+        pb[kt] = ld128(rk, k_off + (unsigned)(16 * a.Hkv * DH * 2) + kt * 64);
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) pv[dt] = ld128(rv, v_off + dt * 16 * 32 * 2);
+    };
+    load_kv(w, nka, nkbv, nvt);
+    for (int kb = w; kb < nkb; kb += NCW) {
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+        ka[kt] = nka[kt];
+        kbv[kt] = nkbv[kt];
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) vt[dt] = nvt[dt];
+      load_kv(kb + NCW, nka, nkbv, nvt);  // the next block's tiles travel while this one is used
+      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) {
+        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt]), q[kt], sa, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbv[kt]), q[kt], sb, 0, 0, 0);
+      }
+      // lane holds keys kb*32 + 4 q4 + i (sa) and kb*32 + 16 + 4 q4 + i (sb) of q-row c16
+      float sv[8];
+      bool ok[8];
+      float mx = -1e30f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        int key = kb * 32 + (i >> 2) * 16 + 4 * q4 + (i & 3);
+        sv[i] = i < 4 ? sa[i] : sb[i - 4];
+        ok[i] = key < L || (key < total && ((vb >> (key - L)) & 1ull));
+        if (ok[i]) mx = fmaxf(mx, sv[i]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      float m_new = fmaxf(m_run, mx);
+      float corr = __expf(m_run - m_new);
+      float p[8], ps = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        p[i] = ok[i] ? __expf(sv[i] - m_new) : 0.f;
+        ps += p[i];
+      }
+      ps += __shfl_xor(ps, 16, 64);
+      ps += __shfl_xor(ps, 32, 64);
+      l_run = l_run * corr + ps;
+      m_run = m_new;
+      u32x4 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+      bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        o[dt] *= corr;
+        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[dt]), pb, o[dt], 0, 0, 0);
+      }
+    }
+    // merge the seven partial results: ((w0 + w4) + (w2 + w6)) + (w3 + (w1 + w5))
+    auto put = [&](int buf) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) red[(buf * RED_TILES + dt) * 64 + lane] = o[dt];
+      mlb[(buf * 64 + lane) * 2] = m_run;
+      mlb[(buf * 64 + lane) * 2 + 1] = l_run;
+    };
+    auto merge = [&](int buf) {
+      float mo = mlb[(buf * 64 + lane) * 2], lo = mlb[(buf * 64 + lane) * 2 + 1];
+      float m_new = fmaxf(m_run, mo);
+      float ca = __expf(m_run - m_new), cb = __expf(mo - m_new);
+      l_run = l_run * ca + lo * cb;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * ca + red[(buf * RED_TILES + dt) * 64 + lane] * cb;
+      m_run = m_new;
+    };
+    const unsigned qs = wv.tree_seq;
+    auto signal = [&](unsigned v) {
+      if (lane == 0) ctl_write(wv.ctl + 4 * (C_TREE + w), v);
+    };
+    if (w >= 4) { put(w - 4); signal(qs + 1); }
+    if (w < 3) { if (!ctl_wait_ge(wv, C_TREE + w + 4, qs + 1)) return false; merge(w); }
+    if (w == 2) { put(2); signal(qs + 2); }
+    if (w == 1) { put(1); signal(qs + 2); }
+    if (w == 0) { if (!ctl_wait_ge(wv, C_TREE + 2, qs + 2)) return false; merge(2); }
+    if (w == 3) { if (!ctl_wait_ge(wv, C_TREE + 1, qs + 2)) return false; merge(1); put(1); signal(qs + 3); }
+    if (w == 0) {
+      if (!ctl_wait_ge(wv, C_TREE + 3, qs + 3)) return false;
+      merge(1);
+      // o[dt][i] = O^T[channel 16 dt + 4 q4 + i][q-row c16]: four channels = half a 16-byte piece
+      if (b < a.Bp) {
+        const float inv = 1.0f / l_run;
+        const int j = rt / a.MT;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          int col = (kvh * g + j) * DH + 16 * dt + 8 * (q4 >> 1);
+          st64(ra, frag_piece(col, b, a.MT) + 8 * (q4 & 1),
+               u32x2{pack_bf16(o[dt][0] * inv, o[dt][1] * inv), pack_bf16(o[dt][2] * inv, o[dt][3] * inv)});
+        }
+      }
+      signal(qs + 4);
+    }
+    wv.tree_seq = qs + 4;
+    // the buffers are free again once wave 0 has read the last of them
+    if (!ctl_wait_ge(wv, C_TREE + 0, qs + 4)) return false;
+  }
+  return true;
+}
+
+// Arg-max over the partial records; logits carry the row's norm factor from here on.
+// One wave per row.
+__device__ __forceinline__ void unembed_final_phase(const StackArgs &a, const Wave &wv) {
+  __amdgpu_buffer_rsrc_t ru = rsrc_of(a.un_part);
+  const int n_part = gridDim.x * a.un_parts_per_cu;
+  for (int b = blockIdx.x * NCW + wv.w; b < a.Bp; b += gridDim.x * NCW) {
+    Top best{-INFINITY, 0x7fffffff, -INFINITY};
+    for (int s = wv.lane; s < n_part; s += 64) {
+      unsigned o = (unsigned)(((size_t)s * 64 + b) * sizeof(Top));
+      Top c{ld32f(ru, o), (int)__builtin_amdgcn_raw_buffer_load_b32(ru, o + 4, 0, DEV), ld32f(ru, o + 8)};
+      best = top_merge2(best, c);
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      Top other;
+      other.v1 = __shfl_xor(best.v1, o, 64);
+      other.i1 = __shfl_xor(best.i1, o, 64);
+      other.v2 = __shfl_xor(best.v2, o, 64);
+      best = top_merge2(best, other);
+    }
+    float s = 0.f;
+    for (int c = wv.lane; c < a.ncg; c += 64) s += ld32f(rsrc_of(a.rsq), (unsigned)((size_t)b * a.ncg + c) * 4);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (wv.lane == 0) {
+      float rsf = 1.0f / sqrtf(s * a.inv_d + a.eps);
+      a.ids[b] = best.i1;
+      if (a.top2) {
+        a.top2[b * 2] = best.v1 * rsf;
+        a.top2[b * 2 + 1] = best.v2 * rsf;
+      }
+    }
+  }
+}
+
+// ---- the persistent kernel ------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t lds_generic[];
+  const lds_t lds = (lds_t)lds_generic;
+  const int L = uni(*a.L_dev);
+  if (L < 0 || L + a.Bp > a.max_len) {  // every workgroup takes the same exit: no barrier is left waiting
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.err = 1;
+    return;
+  }
+  if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + LDS_CTL))[threadIdx.x] = 0u;
+  __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const unsigned ctl = (unsigned)(uintptr_t)(lds + LDS_CTL);
+
+  // this CU's share of each GEMM, in fragments
+  const unsigned f_qkv = (unsigned)(my_tiles(a.qkv.ntiles) * a.qkv.KT), f_o = (unsigned)(my_tiles(a.o.ntiles) * a.o.KT);
+  const unsigned f_gu = (unsigned)(my_tiles(a.gu.ntiles) * a.gu.KT), f_down = (unsigned)(my_tiles(a.down.ntiles) * a.down.KT);
+  const unsigned f_layer = (f_qkv + f_o + f_gu + f_down + CHUNK - 1) / CHUNK * CHUNK;  // padded to whole chunks
+  const unsigned f_un = ((unsigned)(my_tiles(a.un.ntiles) * a.un.KT) + CHUNK - 1) / CHUNK * CHUNK;
+
+  if (wave == NCW) {
+    unsigned long long *st = a.trace ? a.trace + 4 * a.trace_phases + 8 * blockIdx.x : nullptr;
+    if (a.mode == 0) producer(a, ctl, lds + LDS_RING, (unsigned)a.lb, (unsigned)(a.le - a.lb), f_layer, a.seg_frags, st);
+    else producer(a, ctl, lds + LDS_RING, 0u, 1u, f_un, a.seg_frags, st);
+    return;
+  }
+
+  Wave wv;
+  wv.ctl = ctl;
+  wv.w = wave;
+  wv.lane = threadIdx.x & 63;
+  wv.cbar_seq = 0;
+  wv.tree_seq = 0;
+  wv.seen = 0;
+  wv.wait_ticks = 0;
+  wv.dead = false;
+  unsigned epoch = a.epoch0;
+
+  // Phase list.  Layer stack: PREP, then per layer QKV, ATT, O, GU, DOWN.  Unembedding: PREP,
+  // GEMM, FINAL.  One loop with one GEMM call site keeps the kernel's code small.
+  const int n_phases = a.mode == 1 ? 3 : 1 + 5 * (a.le - a.lb);
+  unsigned sbase = 0;
+  for (int ph = 0; ph < n_phases; ++ph) {
+    if (ph > 0 && !grid_sync(a, wv, ++epoch)) return;
+    trace_mark(a, wv, ph, 0);
+    wv.trace_phase = ph;
+    const int sub = a.mode == 1 ? (ph == 0 ? 0 : ph == 1 ? 6 : 7) : (ph == 0 ? 0 : 1 + (ph - 1) % 5);
+    const int layer = a.mode == 1 ? 0 : (ph == 0 ? a.lb : a.lb + (ph - 1) / 5);
+    uint16_t *Kc = a.K + (size_t)layer * a.layer_elems, *Vc = a.V + (size_t)layer * a.layer_elems;
+    // write-once buffers of this layer: fragments of the attn-norm and mlp-norm inputs with
+    // their statistics, the attention output, the SwiGLU output
+    uint16_t *xa0 = a.xa + (size_t)(2 * layer) * a.xa_stride, *xa1 = xa0 + a.xa_stride;
+    float *rsq0 = a.rsq + (size_t)(2 * layer) * a.rsq_stride, *rsq1 = rsq0 + a.rsq_stride;
+    uint16_t *attn_l = a.attn_a + (size_t)layer * a.attn_stride, *act_l = a.act_a + (size_t)layer * a.act_stride;
+    GemmIo io{};
+    const GemmDev *g = nullptr;
+    bool need_rs = false;
+    unsigned frags = 0;
+    switch (sub) {
+      case 0:  // first operand of the launch
+        if (a.mode == 1) {
+          prep_phase(a, wv, a.g_final, a.xa, a.rsq);
+        } else {
+          prep_phase(a, wv, a.gains[layer].g_attn, xa0, rsq0);
+          rope_table_phase(a, wv);
+        }
+        break;
+      case 1:
+        io.A = xa0; io.mode = MODE_QKV; io.rsq_in = rsq0; io.Kc = Kc; io.Vc = Vc; io.L = L;
+        g = &a.qkv; need_rs = true; frags = f_qkv;
+        break;
+      case 2:
+        if (a.dh == 128) { if (!attention_phase<128>(a, wv, lds, Kc, Vc, attn_l, L)) return; }
+        else { if (!attention_phase<64>(a, wv, lds, Kc, Vc, attn_l, L)) return; }
+        break;
+      case 3:
+        io.A = attn_l; io.mode = MODE_RESID; io.gain = a.gains[layer].g_mlp; io.xa_out = xa1; io.rsq_out = rsq1;
+        g = &a.o; frags = f_o;
+        break;
+      case 4:
+        io.A = xa1; io.mode = MODE_GATEUP; io.rsq_in = rsq1; io.act_a = act_l;
+        g = &a.gu; need_rs = true; frags = f_gu;
+        break;
+      case 5:
+        // the fragments feed the next layer's QKV GEMM; the last layer of the call needs none
+        io.A = act_l; io.mode = MODE_RESID;
+        io.gain = layer + 1 < a.le ? a.gains[layer + 1].g_attn : nullptr;
+        io.xa_out = xa0 + 2 * a.xa_stride; io.rsq_out = rsq0 + 2 * a.rsq_stride;
+        g = &a.down; frags = f_layer - f_qkv - f_o - f_gu;  // with the layer's padding
+        break;
+      case 6: {
+        // every CU writes all of its partial records: the ones it has no tiles for stay empty
+        __amdgpu_buffer_rsrc_t rp = rsrc_of(a.un_part);
+        constexpr int tpc_max = RED_TILES / MT;
+        int nt = my_tiles(a.un.ntiles), used = 0;
+        for (int t0 = 0; t0 < nt; t0 += a.un.ntp) used += ((nt - t0 < a.un.ntp ? nt - t0 : a.un.ntp) + tpc_max - 1) / tpc_max;
+        for (int it = wv.w * 64 + wv.lane; it < (a.un_parts_per_cu - used) * 64; it += CONS_THREADS) {
+          unsigned o = (unsigned)(((size_t)(blockIdx.x * a.un_parts_per_cu + used + (it >> 6)) * 64 + (it & 63)) * sizeof(Top));
+          st32f(rp, o, -INFINITY);
+          __builtin_amdgcn_raw_buffer_store_b32(0x7fffffffu, rp, o + 4, 0, DEV);
+          st32f(rp, o + 8, -INFINITY);
+        }
+        io.A = a.xa; io.mode = MODE_UNEMBED; io.un_part = a.un_part + (size_t)blockIdx.x * a.un_parts_per_cu * 64;
+        g = &a.un; frags = f_un;
+        break;
+      }
+      default:
+        unembed_final_phase(a, wv);
+        break;
+    }
+    if (g) {
+      if (!gemm_phase<MT>(a, wv, lds, io, *g, sbase, need_rs)) return;
+      sbase += frags;
+    }
+    trace_mark(a, wv, ph, 2);
+  }
+}
+
+// Launches the persistent kernel for MT row tiles (explicitly instantiated in la_stack_mt*.hip,
+// one translation unit per MT so that they compile in parallel).
+template <int MT>
+int launch_stack_kernel(const StackArgs &a, int n_wgs, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    LA_HIP(hipFuncSetAttribute((const void *)stack_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    attr_set = true;
+  }
+  stack_kernel<MT><<<n_wgs, WG_THREADS, LDS_BYTES, s>>>(a);
+  LA_HIP(hipGetLastError());
+  return LA_OK;
+}
+
+}  // namespace la

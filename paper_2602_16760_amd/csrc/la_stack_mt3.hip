@@ -1,0 +1,6 @@
+// The persistent kernel for blocks of up to 48 rows.
+#include "la_stack.h"
+
+namespace la {
+template int launch_stack_kernel<3>(const StackArgs &, int, hipStream_t);
+}  // namespace la
