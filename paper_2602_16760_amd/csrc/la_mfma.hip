@@ -143,7 +143,7 @@ int mfma_supported(const la_model_desc *d) {
   if (d->d_model % 64 || qd % 32 || d->d_ffn % 32 || nqkv % 16 || d->vocab % 16) return 0;
   if (d->head_dim != 64 && d->head_dim != 128) return 0;
   if (d->n_q_heads / d->n_kv_heads > 8) return 0;
-  if (d->d_model / 16 > 1024) return 0;
+  if (d->d_model / 16 > 512) return 0;  // the row statistics are read as two 128-bit vectors per lane
   // operand buffers are addressed through 32-bit buffer offsets
   size_t lim = (size_t)1 << 31;
   if ((size_t)LA_MAX_ROWS * d->d_ffn * 2 >= lim) return 0;
@@ -220,9 +220,9 @@ int mfma_create(la_model *m) {
   LA_HIP(hipMemset(f->zero_len, 0, 8));
   if (env_int("LA_TRACE", 0)) {
     f->trace_phases = 2 + 5 * d.n_layers;
-    f->trace = (unsigned long long *)dalloc(((size_t)4 * f->trace_phases + 8 * f->n_wgs) * 8);
+    f->trace = (unsigned long long *)dalloc(((size_t)TRACE_SLOTS * f->trace_phases + 8 * f->n_wgs) * 8);
     LA_REQUIRE(f->trace != nullptr, LA_ENOMEM, "device allocation failed");
-    LA_HIP(hipMemset(f->trace, 0, ((size_t)4 * f->trace_phases + 8 * f->n_wgs) * 8));
+    LA_HIP(hipMemset(f->trace, 0, ((size_t)TRACE_SLOTS * f->trace_phases + 8 * f->n_wgs) * 8));
   }
   return LA_OK;
 }
@@ -317,20 +317,26 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
   if (rc) return rc;
   if (f->trace) {  // debugging aid: timeline of workgroup 0 (100 MHz clock) and producer statistics
     int np = n_barriers + 1;
-    std::vector<unsigned long long> h((size_t)4 * f->trace_phases + 8 * f->n_wgs);
+    std::vector<unsigned long long> h((size_t)TRACE_SLOTS * f->trace_phases + 8 * f->n_wgs);
     LA_HIP(hipStreamSynchronize(s));
     LA_HIP(hipMemcpy(h.data(), f->trace, h.size() * 8, hipMemcpyDeviceToHost));
-    fprintf(stderr, "[la trace] %s: %d phases, total %.1f us\n", name, np, (h[4 * (np - 1) + 2] - h[0]) * 0.01);
+    const int S = TRACE_SLOTS;
+    fprintf(stderr, "[la trace] %s: %d phases, total %.1f us (times below: us after the phase's start, workgroup 0 wave 0)\n", name, np,
+            (h[S * (np - 1) + 2] - h[0]) * 0.01);
     for (int q = 0; q < np && q < 12; ++q) {
-      double wait = q > 0 ? (h[4 * q] - h[4 * (q - 1) + 2]) * 0.01 : 0.0;
-      fprintf(stderr, "[la trace]   phase %2d: barrier %6.2f us  work %7.2f us", q, wait, (h[4 * q + 2] - h[4 * q]) * 0.01);
-      if (h[4 * q + 1] > h[4 * q])
-        fprintf(stderr, "  (k-loop %7.2f us, of it waiting for weights %7.2f us)", (h[4 * q + 1] - h[4 * q]) * 0.01, h[4 * q + 3] * 0.01);
-      fprintf(stderr, "\n");
+      const unsigned long long t0 = h[S * q];
+      auto rel = [&](int k) { return h[S * q + k] > t0 ? (h[S * q + k] - t0) * 0.01 : -1.0; };
+      double since_prev = q > 0 ? (t0 - h[S * (q - 1) + 2]) * 0.01 : 0.0;
+      fprintf(stderr, "[la trace]   phase %2d: +%5.2f | pass entry %5.2f loop start %5.2f 2nd batch %5.2f | k-loop end %6.2f (waited for weights %6.2f) tile %6.2f epilogue %6.2f | attn: loads %6.2f loop %6.2f merged %6.2f | "
+              "work end %6.2f | barrier: stores %6.2f waves %6.2f released %6.2f\n", q, since_prev, rel(13), rel(14), rel(15), rel(1), h[S * q + 1] > t0 ? h[S * q + 3] * 0.01 : -1.0,
+              rel(4), rel(5), rel(9), rel(10), rel(11), rel(2), rel(6), rel(7), rel(8));
     }
+    if (np > 1 && h[S * (np - 1)] > h[0])
+      fprintf(stderr, "[la trace]   shader clock over the launch: %.0f MHz\n",
+              (double)(h[S * (np - 1) + 12] - h[12]) / ((h[S * (np - 1)] - h[0]) * 0.01));
     double st[6] = {0, 0, 0, 0, 0, 0};
     for (int g = 0; g < f->n_wgs; ++g)
-      for (int k = 0; k < 6; ++k) st[k] += (double)h[(size_t)4 * f->trace_phases + 8 * g + k] / f->n_wgs;
+      for (int k = 0; k < 6; ++k) st[k] += (double)h[(size_t)TRACE_SLOTS * f->trace_phases + 8 * g + k] / f->n_wgs;
     fprintf(stderr, "[la trace]   producer (mean per workgroup): ring full %.1f times, %.1f polls; of %.1f us: draining before a poll %.1f us, "
             "polling for space %.1f us, waiting for the oldest chunk %.1f us\n", st[1], st[0], st[5] * 0.01, st[2] * 0.01, st[3] * 0.01, st[4] * 0.01);
   }
@@ -372,6 +378,7 @@ static StackArgs base_stack_args(la_model *m, int Bp) {
   a.rsq = f->rsq;
   a.cs = m->rope_cs;
   a.sync = f->sync;
+  a.dbg = env_int("LA_DBG", 0);
   a.qkv = dev_plan(f->p_qkv);
   a.o = dev_plan(f->p_o);
   a.gu = dev_plan(f->p_gu);

@@ -63,6 +63,7 @@ constexpr int MAX_MT = LA_MAX_ROWS / 16;
 constexpr unsigned OOB = 0x80000000u;      // voffset beyond every buffer (all are < 2 GiB)
 constexpr unsigned RSRC_BYTES = 0x7fffffffu;
 constexpr int DEV = 16;                    // cache policy sc1: device-scope coherent load / store
+constexpr int TRACE_SLOTS = 16;            // timestamps per phase of the optional timeline
 constexpr int NT_HINT = 2;                 // cache policy nt: streamed once
 constexpr int SYNC_GROUP = 16;             // workgroups per arrival counter of the grid barrier
 constexpr int SYNC_STRIDE = 64;            // 32-bit words between barrier variables (256 B)
@@ -75,7 +76,9 @@ constexpr int LDS_RED = NSLOT * 1024;                 // 3 buffers of RED_TILES 
 constexpr int LDS_ML = LDS_RED + 3 * RED_TILES * 1024;  // attention: running max / sum per wave and lane
 constexpr int LDS_RS = LDS_ML + 4 * 512;              // [64] row factors of the norm
 constexpr int LDS_CTL = LDS_RS + 256;                 // control words
-constexpr int LDS_BYTES = LDS_CTL + 256;
+constexpr int LDS_CONST = LDS_CTL + 256;                // per-launch constants (LaunchConst)
+constexpr int LDS_ARGS = LDS_CONST + 128;               // per consumer wave: arguments of the GEMM pass it calls (PassArgs)
+constexpr int LDS_BYTES = LDS_ARGS + NCW * 128;
 // control words
 constexpr int C_LANDED = 0;   // fragments of this workgroup's stream that have landed in the ring
 constexpr int C_DEAD = 1;     // a wait timed out: every wave leaves the kernel
@@ -114,6 +117,7 @@ struct LayerGains {
 struct StackArgs {
   const LayerGains *gains;
   int mode;  // 0: layer stack, 1: unembedding
+  int dbg;   // timing experiments (results are wrong when set): 1 producer moves nothing, 2 one operand k-tile, 4 no operand loads, 8 no epilogue
   int lb, le;
   int Bp, MT, d, Hq, Hkv, dh, F, ncg;
   float eps, inv_d;
@@ -158,6 +162,47 @@ __device__ __forceinline__ T *uni_ptr(T *p) {
   return (T *)(((uint64_t)hi << 32) | lo);
 }
 
+// Per-launch constants every phase function needs, kept in LDS so that they need not travel as
+// arguments (a function's arguments beyond 32 registers go through memory).
+struct LaunchConst {
+  int Bp, MT, d, ncg, Hq, Hkv, dh, L, dbg;
+  float inv_d, eps;
+  float *x;
+  const float *cs;
+  uint16_t *qf;
+};
+static_assert(sizeof(LaunchConst) <= 128, "LDS_CONST region");
+__device__ __forceinline__ LaunchConst launch_const(unsigned lds0) {
+  LDS_AS const LaunchConst *p = (LDS_AS const LaunchConst *)(uintptr_t)(lds0 + LDS_CONST);
+  LaunchConst c;
+  c.Bp = uni(p->Bp); c.MT = uni(p->MT); c.d = uni(p->d); c.ncg = uni(p->ncg); c.Hq = uni(p->Hq); c.Hkv = uni(p->Hkv);
+  c.dh = uni(p->dh); c.L = uni(p->L); c.dbg = uni(p->dbg);
+  c.inv_d = __uint_as_float(uni(__float_as_uint(p->inv_d)));
+  c.eps = __uint_as_float(uni(__float_as_uint(p->eps)));
+  c.x = uni_ptr(p->x); c.cs = uni_ptr(p->cs); c.qf = uni_ptr(p->qf);
+  return c;
+}
+
+// Plain structs to and from LDS, word by word (a struct cannot be copied across address spaces).
+template <typename T>
+__device__ __forceinline__ T lds_get(unsigned addr) {
+  static_assert(sizeof(T) % 4 == 0, "whole words");
+  T v;
+  LDS_AS const unsigned *src = (LDS_AS const unsigned *)(uintptr_t)addr;
+  unsigned *dst = reinterpret_cast<unsigned *>(&v);
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(T) / 4; ++i) dst[i] = src[i];
+  return v;
+}
+template <typename T>
+__device__ __forceinline__ void lds_put(unsigned addr, const T &v) {
+  static_assert(sizeof(T) % 4 == 0, "whole words");
+  LDS_AS unsigned *dst = (LDS_AS unsigned *)(uintptr_t)addr;
+  const unsigned *src = reinterpret_cast<const unsigned *>(&v);
+#pragma unroll
+  for (unsigned i = 0; i < sizeof(T) / 4; ++i) dst[i] = src[i];
+}
+
 // ---- LDS control words: inline assembly, so that the compiler neither caches them nor puts
 // waits for the producer's outstanding direct-to-LDS loads in front of them --------------------
 __device__ __forceinline__ unsigned ctl_read(unsigned addr) {
@@ -181,15 +226,19 @@ __device__ __forceinline__ void wait_vmcnt() {  // at most N vector-memory opera
   __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-struct Wave {          // per-wave view of the workgroup's LDS and sequence numbers
+// Sequence numbers a consumer wave carries from phase to phase (all waves hold the same
+// values), passed by value into and out of the phase functions.
+struct WaveState {
+  unsigned cbar_seq;   // consumer barrier: arrivals expected so far
+  unsigned tree_seq;   // hand-off sequence of the reduction tree
+  unsigned seen;       // cached copy of C_LANDED
+  int ok;              // 0 after a wait timed out: the wave leaves the kernel
+};
+
+struct Wave {          // a wave's view inside one function
   unsigned ctl;        // LDS byte address of the control words
   int w, lane;
-  unsigned cbar_seq;   // consumer barrier: arrivals expected so far
-  unsigned tree_seq;   // hand-off sequence
-  unsigned seen;       // cached copy of C_LANDED
-  int trace_phase;
-  unsigned long long wait_ticks;  // tracing: time spent waiting for weights to land
-  bool dead;
+  WaveState st;
 };
 
 // Spin until the control word reaches `want`.  Returns false (and raises C_DEAD) on a timeout
@@ -204,7 +253,7 @@ __device__ __forceinline__ bool ctl_wait_ge(Wave &wv, int word, unsigned want) {
     if ((spins & 255u) == 0) {
       if (ctl_read(wv.ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS) {
         ctl_write(wv.ctl + 4 * C_DEAD, 1u);
-        wv.dead = true;
+        wv.st.ok = 0;
         return false;
       }
     }
@@ -214,9 +263,14 @@ __device__ __forceinline__ bool ctl_wait_ge(Wave &wv, int word, unsigned want) {
 // Barrier of the seven consumer waves.  LDS executes one wave's operations in order, so the
 // data a wave wrote before arriving is visible to every wave that has seen the arrival.
 __device__ __forceinline__ bool cons_barrier(Wave &wv) {
-  wv.cbar_seq += NCW;
+  wv.st.cbar_seq += NCW;
   if (wv.lane == 0) ctl_add(wv.ctl + 4 * C_CBAR, 1u);
-  return ctl_wait_ge(wv, C_CBAR, wv.cbar_seq);
+  return ctl_wait_ge(wv, C_CBAR, wv.st.cbar_seq);
+}
+
+// Timeline of workgroup 0, wave 0 (tracing only): tr is null everywhere else.
+__device__ __forceinline__ void tr_mark(unsigned long long *tr, const Wave &wv, int k) {
+  if (tr && wv.w == 0 && wv.lane == 0) tr[k] = wall_clock64();
 }
 
 // ---- device-scope accessors ------------------------------------------------------------------
@@ -250,10 +304,6 @@ __device__ __forceinline__ unsigned frag_piece(int col, int b, int MT) {
   return (unsigned)((((size_t)(col >> 5) * MT + (b >> 4)) * 64 + (b & 15) + 16 * ((col & 31) >> 3)) * 16);
 }
 
-__device__ __forceinline__ void trace_mark(const StackArgs &a, const Wave &wv, int phase, int k) {
-  if (a.trace && blockIdx.x == 0 && wv.w == 0 && wv.lane == 0 && phase < a.trace_phases) a.trace[4 * phase + k] = wall_clock64();
-}
-
 // tiles of a matrix that belong to this CU (tile t -> CU t mod G)
 __device__ __forceinline__ int my_tiles(int ntiles) {
   int c = blockIdx.x, G = gridDim.x;
@@ -266,10 +316,12 @@ __device__ __forceinline__ int my_tiles(int ntiles) {
 // atomics: the data exchanged between workgroups travels with sc1 accesses, and each wave waits
 // for its own stores before the workgroup arrives.  Every spin is bounded: on a timeout the
 // error flag is raised and the workgroup leaves the kernel (the others then time out too).
-__device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned epoch) {
+__device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned epoch, unsigned long long *tr) {
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
   wait_vmcnt<0>();  // this wave's stores are acknowledged
+  tr_mark(tr, wv, 6);
   if (!cons_barrier(wv)) return false;
+  tr_mark(tr, wv, 7);
   if (wv.w == 0) {
     if (wv.lane == 0) {
       unsigned n = gridDim.x;
@@ -295,7 +347,9 @@ __device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned
       else ctl_write(wv.ctl + 4 * C_DEAD, 1u);
     }
   }
-  return ctl_wait_ge(wv, C_GPASS, epoch);
+  const bool ok = ctl_wait_ge(wv, C_GPASS, epoch);
+  tr_mark(tr, wv, 8);
+  return ok;
 }
 
 // ---- producer ----------------------------------------------------------------------------------
@@ -320,6 +374,10 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
   unsigned long long t_drain = 0, t_poll = 0, t_flight = 0;
   const bool tr = stats != nullptr;
   const unsigned long long t_begin = tr ? wall_clock64() : 0ull;
+  if (a.dbg & 1) {
+    ctl_write(ctl + 4 * C_LANDED, total);
+    return;
+  }
   while (next < total) {
     if (next + CHUNK > free_until) {
       // ring full: publish everything in flight, then poll the consumers
@@ -391,23 +449,14 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
 
 // ---- GEMM pass (consumer waves) --------------------------------------------------------------
 template <int MT, int NT>
-struct Depth {  // k-tiles of the activation operand in flight per wave
-  static constexpr int raw = (176 - 4 * MT * NT - 4 * NT) / (4 * MT);
-  static constexpr int value = raw < 2 ? 2 : (raw > 6 ? 6 : raw);
-};
-
-struct GemmIo {
-  const uint16_t *A;      // operand fragments (a write-once buffer: loaded through the cache)
-  int mode;
-  const float *rsq_in;    // MODE_QKV, MODE_GATEUP: sums of squares of the input rows [64][ncg]
-  uint16_t *Kc, *Vc;      // MODE_QKV: this layer's cache
-  int L;
-  const float *gain;      // MODE_RESID: gain of the next norm (nullptr: no fragments wanted)
-  uint16_t *xa_out;       // MODE_RESID: fragments of x * gain for the next GEMM
-  float *rsq_out;         // MODE_RESID: sums of squares of the new x
-  uint16_t *act_a;        // MODE_GATEUP: fragments for the down projection
-  Top *un_part;           // MODE_UNEMBED
-  int part0;              // MODE_UNEMBED: index of this pass's first partial record
+struct Depth {  // k-tiles per batch of a wave = depth of its activation-operand prefetch
+  // registers: DA operand fragments per row tile beside the accumulators and one k-tile of weights
+  static constexpr int by_regs = (200 - 4 * MT * NT - 4 * NT) / (4 * MT);
+  // ring: the batch of the last wave (k-tiles 6, 13, ..) must fit the ring together with what the
+  // first wave still holds: (6 + 7 (DA - 1) + 1) NT <= NSLOT - CHUNK
+  static constexpr int by_ring = ((NSLOT - CHUNK) / NT - NCW) / NCW + 1;
+  static constexpr int m = by_regs < by_ring ? by_regs : by_ring;
+  static constexpr int value = m < 1 ? 1 : (m > 12 ? 12 : m);
 };
 
 // Row factors rsqrt(mean(x^2) + eps) of the block's rows into LDS: wave w takes rows w, w+7, ...
@@ -415,66 +464,252 @@ struct GemmIo {
 template <int MT>
 struct RowStat {
   static constexpr int NR = (16 * MT + NCW - 1) / NCW;
-  f32x4 v[NR];
+  f32x4 v[NR][2];
 };
 template <int MT>
-__device__ __forceinline__ void rowstat_load(const StackArgs &a, const Wave &wv, const float *rsq_in, RowStat<MT> &rs) {
-  // ncg / 4 vectors per row; rows are short (ncg <= 1024): lanes beyond the row read nothing
+__device__ __forceinline__ void rowstat_load(int Bp, int ncg, const Wave &wv, const float *rsq_in, RowStat<MT> &rs) {
+  // ncg / 4 <= 128 vectors per row: two per lane, no branches (beyond the row or the block:
+  // out-of-range loads that move nothing and return zeros)
+  __amdgpu_buffer_rsrc_t rr = rsrc_of(rsq_in);
 #pragma unroll
   for (int i = 0; i < RowStat<MT>::NR; ++i) {
-    int row = wv.w + NCW * i;
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    if (row < a.Bp)
-      for (int c4 = wv.lane; c4 < a.ncg / 4; c4 += 64) {
-        f32x4 t = *reinterpret_cast<const f32x4 *>(rsq_in + (size_t)row * a.ncg + 4 * c4);
-        s += t;
-      }
-    rs.v[i] = s;
+    const int row = wv.w + NCW * i;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int c4 = wv.lane + 64 * j;
+      const unsigned vo = (row < Bp && c4 < (ncg >> 2)) ? (unsigned)c4 * 16u : OOB;
+      rs.v[i][j] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rr, vo, (unsigned)(row * ncg) * 4u, 0));
+    }
   }
 }
 template <int MT>
-__device__ __forceinline__ void rowstat_finish(const StackArgs &a, const Wave &wv, const RowStat<MT> &rs, LDS_AS float *rs_lds) {
+__device__ __forceinline__ void rowstat_finish(int Bp, float inv_d, float eps, const Wave &wv, const RowStat<MT> &rs,
+                                               LDS_AS float *rs_lds) {
 #pragma unroll
   for (int i = 0; i < RowStat<MT>::NR; ++i) {
     int row = wv.w + NCW * i;
-    float s = (rs.v[i][0] + rs.v[i][1]) + (rs.v[i][2] + rs.v[i][3]);
+    f32x4 t = rs.v[i][0] + rs.v[i][1];
+    float s = (t[0] + t[1]) + (t[2] + t[3]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-    if (row < 16 * MT && wv.lane == 0) rs_lds[row] = row < a.Bp ? 1.0f / sqrtf(s * a.inv_d + a.eps) : 0.f;
+    if (row < 16 * MT && wv.lane == 0) rs_lds[row] = row < Bp ? 1.0f / sqrtf(s * inv_d + eps) : 0.f;
   }
 }
 
+// ---- GEMM epilogues ----------------------------------------------------------------------------
+// Run by all consumer waves on a finished chunk of the result (rows x ntc column tiles, row-major
+// in LDS).  A function of its own, with everything it needs passed by value: it runs once per
+// chunk, and keeping it out of the GEMM loops keeps their register allocation free of it.
+// (Two structs: an aggregate of more than 64 bytes is passed through memory.)
+struct EpiPtrs {
+  uint16_t *Kc, *Vc;
+  const float *gain;
+  uint16_t *xa_out;
+  float *rsq_out;
+  uint16_t *act_a;
+  Top *un_part;
+};
+struct EpiInts {
+  int mode, tile_first, ntc, LDT, part, tid;
+  unsigned lds0;  // LDS byte address of the kernel's dynamic LDS
+};
+static_assert(sizeof(EpiPtrs) <= 64 && sizeof(EpiInts) <= 64, "passed in registers");
+
+// Everything one GEMM pass needs.  The pass is a function of its own (one per number of column
+// tiles), so that its loops get registers of their own and nothing of the rest of the kernel is
+// kept alive, or spilled, across them.  The caller leaves the arguments in the wave's slot of
+// LDS_ARGS: arguments beyond 32 registers would travel through scratch memory, whose latency is
+// that of a global load.
+struct alignas(16) PassArgs {
+  EpiPtrs q;               // epilogue outputs
+  int mode;                // epilogue (GemmMode)
+  const uint16_t *A;       // operand fragments (a write-once buffer: loaded through the cache)
+  const float *rsq_in;     // sums of squares of the input rows [64][ncg], or null: no row factors
+  int KT, tile0, part0;
+  unsigned sbase;          // index in the workgroup's stream of the pass's first fragment
+  unsigned long long *tr;  // timeline slots of this phase (workgroup 0 only) or null
+};
+
 // One pass: NT column tiles of this CU (local tiles tile0 .. tile0+NT-1), the whole contraction.
-// sbase = index in the workgroup's stream of the pass's first fragment.
+static_assert(sizeof(PassArgs) <= 128, "LDS_ARGS slot");
+
+__device__ __attribute__((noinline)) void gemm_epilogue(EpiInts e) {
+  const unsigned lds0 = uni(e.lds0);
+  const EpiPtrs q = lds_get<EpiPtrs>(lds0 + LDS_ARGS + 128 * uni(e.tid >> 6));  // first member of the wave's PassArgs
+  const LaunchConst lc = launch_const(lds0);
+  const int mode = uni(e.mode), Bp = lc.Bp, MT = lc.MT, d = lc.d, ncg = lc.ncg, Hq = lc.Hq, Hkv = lc.Hkv, dh = lc.dh, L = lc.L,
+            tile_first = uni(e.tile_first), ntc = uni(e.ntc), LDT = uni(e.LDT), part = uni(e.part);
+  const int tid = e.tid;
+  const float *cs = lc.cs;
+  LDS_AS const float *tile = (LDS_AS const float *)(uintptr_t)(lds0 + LDS_RED);
+  LDS_AS const float *rs_lds = (LDS_AS const float *)(uintptr_t)(lds0 + LDS_RS);
+  const int G = gridDim.x, cu = blockIdx.x;
+  if (mode == MODE_QKV) {
+    // A tile holds channels 8j..8j+7 (columns 0..7) and dh/2 + 8j.. (columns 8..15) of one
+    // head: both members of eight RoPE pairs.  One thread per (row, tile).
+    for (int it = tid; it < Bp * ntc; it += CONS_THREADS) {
+      const int b = it / ntc, tt = it - b * ntc;
+      const int gt = cu + G * (tile_first + tt);
+      const int half = dh >> 1, spj = dh >> 4, grp = Hq / Hkv;
+      const int hs = gt / spj, j = gt - hs * spj;
+      const float rsf = rs_lds[b];
+      LDS_AS const float *tr = tile + b * LDT + 16 * tt;
+      const float qscale = hs < Hq ? 1.0f / sqrtf((float)dh) : 1.0f;
+      float y0[8], y1[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        float x0 = tr[k] * rsf, x1 = tr[8 + k] * rsf;
+        if (hs < Hq + Hkv) {
+          float c = cs[((size_t)b * half + 8 * j + k) * 2], sn = cs[((size_t)b * half + 8 * j + k) * 2 + 1];
+          y0[k] = (x0 * c - x1 * sn) * qscale;
+          y1[k] = (x1 * c + x0 * sn) * qscale;
+        } else {
+          y0[k] = x0;
+          y1[k] = x1;
+        }
+      }
+      u32x4 lo = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y0[4], y0[5]), pack_bf16(y0[6], y0[7])};
+      u32x4 hi = {pack_bf16(y1[0], y1[1]), pack_bf16(y1[2], y1[3]), pack_bf16(y1[4], y1[5]), pack_bf16(y1[6], y1[7])};
+      const int o_lo = j, o_hi = (half >> 3) + j;  // channel octets of the two pieces
+      if (hs < Hq) {
+        __amdgpu_buffer_rsrc_t rqf = rsrc_of(lc.qf);
+        int kvh = hs / grp, jq = hs - kvh * grp, rt = jq * MT + (b >> 4);
+        size_t fb = ((size_t)kvh * (grp * MT) + rt) * (dh >> 5);
+        st128(rqf, (unsigned)(((fb + (o_lo >> 2)) * 64 + (b & 15) + 16 * (o_lo & 3)) * 16), lo);
+        st128(rqf, (unsigned)(((fb + (o_hi >> 2)) * 64 + (b & 15) + 16 * (o_hi & 3)) * 16), hi);
+      } else if (hs < Hq + Hkv) {
+        __amdgpu_buffer_rsrc_t rk = rsrc_of(q.Kc);
+        size_t rb = ((size_t)(L + b) * Hkv + (hs - Hq)) * dh;
+        st128(rk, (unsigned)((rb + 8 * o_lo) * 2), lo);
+        st128(rk, (unsigned)((rb + 8 * o_hi) * 2), hi);
+      } else {
+        __amdgpu_buffer_rsrc_t rv = rsrc_of(q.Vc);
+        int h = hs - Hq - Hkv;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          st16(rv, (unsigned)(v_index(true, L + b, h, 8 * j + k, Hkv, dh) * 2), float_to_bf16(y0[k]));
+          st16(rv, (unsigned)(v_index(true, L + b, h, half + 8 * j + k, Hkv, dh) * 2), float_to_bf16(y1[k]));
+        }
+      }
+    }
+  } else if (mode == MODE_RESID) {
+    // x[:, tile columns] += tile; sum of squares of the new values; fragments of x * gain.
+    // Two threads per (row, tile), eight columns each.  This workgroup owns these columns of
+    // x in every layer, so x needs no device-scope accesses.
+    for (int it = tid; it < Bp * ntc * 2; it += CONS_THREADS) {
+      const int oct = it & 1, bt = it >> 1;
+      const int b = bt / ntc, tt = bt - b * ntc;
+      const int gt = cu + G * (tile_first + tt);
+      const int col = 16 * gt + 8 * oct;
+      f32x4 *xp = reinterpret_cast<f32x4 *>(lc.x + (size_t)b * d + col);
+      LDS_AS const float *tr = tile + b * LDT + 16 * tt + 8 * oct;
+      f32x4 x0 = xp[0], x1 = xp[1];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x0[i] += tr[i];
+        x1[i] += tr[4 + i];
+      }
+      xp[0] = x0;
+      xp[1] = x1;
+      float sq = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
+      sq += __shfl_xor(sq, 1, 64);
+      if (q.gain) {
+        if (oct == 0) st32f(rsrc_of(q.rsq_out), (unsigned)(b * ncg + gt) * 4, sq);
+        const float *gp = q.gain + col;
+        u32x4 v = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
+                   pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+        st128(rsrc_of(q.xa_out), frag_piece(col, b, MT), v);
+      }
+    }
+  } else if (mode == MODE_GATEUP) {
+    // tile columns: 8 gate channels, then the same 8 channels of up
+    __amdgpu_buffer_rsrc_t rp = rsrc_of(q.act_a);
+    for (int it = tid; it < Bp * ntc; it += CONS_THREADS) {
+      const int b = it / ntc, tt = it - b * ntc;
+      const int gt = cu + G * (tile_first + tt);
+      const float rsf = rs_lds[b];
+      LDS_AS const float *gp = tile + b * LDT + 16 * tt, *up = gp + 8;
+      float act[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        float g = gp[i] * rsf, u = up[i] * rsf;
+        act[i] = g / (1.0f + __expf(-g)) * u;
+      }
+      st128(rp, frag_piece(8 * gt, b, MT),
+            u32x4{pack_bf16(act[0], act[1]), pack_bf16(act[2], act[3]), pack_bf16(act[4], act[5]), pack_bf16(act[6], act[7])});
+    }
+  } else {  // MODE_UNEMBED: arg-max of each row over this chunk's columns, 4 threads per row
+    const int row = tid >> 2, j = tid & 3;
+    Top best{-INFINITY, 0x7fffffff, -INFINITY};
+    if (row < Bp)
+      for (int c = j; c < 16 * ntc; c += 4) {
+        int gt = cu + G * (tile_first + (c >> 4));
+        best = top_merge2(best, Top{tile[row * LDT + c], 16 * gt + (c & 15), -INFINITY});
+      }
+#pragma unroll
+    for (int o = 1; o < 4; o <<= 1) {
+      Top other;
+      other.v1 = __shfl_xor(best.v1, o, 64);
+      other.i1 = __shfl_xor(best.i1, o, 64);
+      other.v2 = __shfl_xor(best.v2, o, 64);
+      best = top_merge2(best, other);
+    }
+    if (j == 0 && row < Bp) {
+      __amdgpu_buffer_rsrc_t rp = rsrc_of(q.un_part);
+      unsigned o = (unsigned)(((size_t)part * 64 + row) * sizeof(Top));
+      st32f(rp, o, best.v1);
+      __builtin_amdgcn_raw_buffer_store_b32((unsigned)best.i1, rp, o + 4, 0, DEV);
+      st32f(rp, o + 8, best.v2);
+    }
+  }
+}
+
+
 template <int MT, int NT>
-__device__ __forceinline__ bool gemm_pass(const StackArgs &a, Wave &wv, lds_t lds, const GemmIo &io, int KT, unsigned sbase,
-                                          int tile0, bool need_rs) {
+__device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveState st_in) {
   constexpr int DA = Depth<MT, NT>::value;
   constexpr int TPC = (RED_TILES / MT) < NT ? (RED_TILES / MT) : NT;  // column tiles per reduction chunk
   constexpr int LDT = 16 * TPC + 4;                                  // padded row length of the result tile
-  const int w = uni(wv.w), lane = wv.lane;
-  KT = uni(KT);
-  sbase = uni(sbase);
-  tile0 = uni(tile0);
-  LDS_AS const u32x4 *ring = (LDS_AS const u32x4 *)(lds + LDS_RING);
-  LDS_AS f32x4 *red = (LDS_AS f32x4 *)(lds + LDS_RED);
-  LDS_AS float *tile = (LDS_AS float *)(lds + LDS_RED);
-  LDS_AS float *rs_lds = (LDS_AS float *)(lds + LDS_RS);
-  __amdgpu_buffer_rsrc_t ra = rsrc_of(io.A);
+  Wave wv;
+  wv.w = uni((int)(threadIdx.x >> 6));
+  wv.lane = threadIdx.x & 63;
+  const unsigned lds0 = uni(lds0_in);
+  const PassArgs p = lds_get<PassArgs>(lds0 + LDS_ARGS + 128 * wv.w);
+  const LaunchConst lc = launch_const(lds0);
+  wv.ctl = lds0 + LDS_CTL;
+  wv.st.cbar_seq = uni(st_in.cbar_seq);
+  wv.st.tree_seq = uni(st_in.tree_seq);
+  wv.st.seen = uni(st_in.seen);
+  wv.st.ok = 1;
+  const int w = wv.w, lane = wv.lane;
+  const int KT = uni(p.KT), tile0 = uni(p.tile0), Bp = lc.Bp, ncg = lc.ncg;
+  const unsigned sbase = uni(p.sbase);
+  unsigned long long *tr = uni_ptr(p.tr);
+  const float *rsq_in = uni_ptr(p.rsq_in);
+  const bool need_rs = rsq_in != nullptr;
+  LDS_AS const u32x4 *ring = (LDS_AS const u32x4 *)(uintptr_t)(lds0 + LDS_RING);
+  LDS_AS f32x4 *red = (LDS_AS f32x4 *)(uintptr_t)(lds0 + LDS_RED);
+  LDS_AS float *tile = (LDS_AS float *)(uintptr_t)(lds0 + LDS_RED);
+  LDS_AS float *rs_lds = (LDS_AS float *)(uintptr_t)(lds0 + LDS_RS);
+  __amdgpu_buffer_rsrc_t ra = rsrc_of(p.A);
   const unsigned voff = lane * 16;
   const int nk = KT > w ? (KT - w + NCW - 1) / NCW : 0;  // this wave's k-tiles: w, w + 7, ...
+  unsigned long long wait_ticks = 0;
+  if (tile0 == 0) tr_mark(tr, wv, 13);
 
   u32x4 rA[DA][MT];
   auto load_a = [&](int slot, int i) {
-    unsigned vo = (i < nk) ? voff : OOB;  // out of range: zeros come back, no memory traffic
-    unsigned kt = (unsigned)(w + NCW * i);
+    unsigned vo = (i < nk && !(lc.dbg & 4)) ? voff : OOB;  // out of range: zeros come back, no memory traffic
+    unsigned kt = (lc.dbg & 2) ? 0u : (unsigned)(w + NCW * i);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) rA[slot][mt] = __builtin_amdgcn_raw_buffer_load_b128(ra, vo, (kt * MT + mt) * 1024u, 0);
   };
 #pragma unroll
   for (int s = 0; s < DA; ++s) load_a(s, s);
   RowStat<MT> rs;
-  if (need_rs) rowstat_load(a, wv, io.rsq_in, rs);
+  if (need_rs) rowstat_load<MT>(Bp, ncg, wv, rsq_in, rs);
 
   f32x4 acc[MT][NT];
 #pragma unroll
@@ -482,54 +717,65 @@ __device__ __forceinline__ bool gemm_pass(const StackArgs &a, Wave &wv, lds_t ld
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // The wave's k-tiles are taken DA at a time.  One wait per batch (for the weights of its last
+  // k-tile), then straight-line code: every slot reads its weights from the ring, multiplies and
+  // requests the operand of the slot's next turn, so the operand prefetch is a full batch deep.
+  // A slot beyond the wave's last k-tile multiplies zeros and loads out of range (nothing moves).
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  if (tile0 == 0) tr_mark(tr, wv, 14);
   for (int i0 = 0; i0 < nk; i0 += DA) {
+    if (tile0 == 0 && i0 == DA) tr_mark(tr, wv, 15);
+    const int last = (i0 + DA < nk ? i0 + DA : nk) - 1;  // the batch's last valid k-tile of this wave
+    const unsigned need = sbase + (unsigned)(w + NCW * last + 1) * NT;
+    if ((int)(wv.st.seen - need) < 0) {
+      unsigned spins = 0;
+      const unsigned long long t0 = tr ? wall_clock64() : 0ull;
+      for (;;) {
+        wv.st.seen = ctl_read(wv.ctl + 4 * C_LANDED);
+        if ((int)(wv.st.seen - need) >= 0) break;
+        __builtin_amdgcn_s_sleep(1);
+        if ((++spins & 255u) == 0 && (ctl_read(wv.ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS)) {
+          ctl_write(wv.ctl + 4 * C_DEAD, 1u);
+          wv.st.ok = 0;
+          return wv.st;
+        }
+      }
+      if (tr) wait_ticks += wall_clock64() - t0;
+    }
 #pragma unroll
     for (int s = 0; s < DA; ++s) {
       const int i = i0 + s;
-      if (i < nk) {
-        const unsigned kt = (unsigned)(w + NCW * i);
-        const unsigned first = sbase + kt * NT;
-        if ((int)(wv.seen - (first + NT)) < 0) {
-          unsigned spins = 0;
-          const unsigned long long t0 = a.trace ? wall_clock64() : 0ull;
-          for (;;) {
-            wv.seen = ctl_read(wv.ctl + 4 * C_LANDED);
-            if ((int)(wv.seen - (first + NT)) >= 0) break;
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 255u) == 0 && (ctl_read(wv.ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS)) {
-              ctl_write(wv.ctl + 4 * C_DEAD, 1u);
-              wv.dead = true;
-              return false;
-            }
-          }
-          if (a.trace) wv.wait_ticks += wall_clock64() - t0;
-        }
-        u32x4 rW[NT];
+      const bool valid = i < nk;
+      const unsigned kt = valid ? (unsigned)(w + NCW * i) : 0u;
+      const unsigned first = sbase + kt * NT;
+      u32x4 rW[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) rW[t] = ring[((first + t) & (NSLOT - 1)) * 64 + lane];
-        // the reads above are in the LDS queue before this write: when the producer sees the
-        // new value, the slots have been read
-        {
-          unsigned nxt = kt + NCW < (unsigned)KT ? kt + NCW : (unsigned)KT;
-          if (lane == 0) ctl_write(wv.ctl + 4 * (C_PROG + w), sbase + nxt * NT);
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int t = 0; t < NT; ++t)
-            acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rA[s][mt]),
-                                                                  __builtin_bit_cast(bf16x8, rW[t]), acc[mt][t], 0, 0, 0);
-        load_a(s, i + DA);
+      for (int t = 0; t < NT; ++t) {
+        u32x4 v = ring[((first + t) & (NSLOT - 1)) * 64 + lane];
+        rW[t] = valid ? v : zero4;
       }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rA[s][mt]),
+                                                                __builtin_bit_cast(bf16x8, rW[t]), acc[mt][t], 0, 0, 0);
+      load_a(s, i + DA);
+    }
+    // the batch's reads are in the LDS queue before this write: when the producer sees the new
+    // value, the slots have been read
+    {
+      const int nxt_i = i0 + DA;
+      const unsigned nxt = nxt_i < nk ? (unsigned)(w + NCW * nxt_i) : (unsigned)KT;
+      if (lane == 0) ctl_write(wv.ctl + 4 * (C_PROG + w), sbase + nxt * NT);
     }
   }
   // nothing of this pass is needed any more (also covers a wave that had no k-tile)
   if (lane == 0) ctl_write(wv.ctl + 4 * (C_PROG + w), sbase + (unsigned)KT * NT);
-  if (need_rs) rowstat_finish(a, wv, rs, rs_lds);
-  if (a.trace && blockIdx.x == 0 && w == 0 && lane == 0 && tile0 == 0 && wv.trace_phase < a.trace_phases) {
-    a.trace[4 * wv.trace_phase + 1] = wall_clock64();
-    a.trace[4 * wv.trace_phase + 3] = wv.wait_ticks;
-    wv.wait_ticks = 0;
+  if (need_rs) rowstat_finish<MT>(Bp, lc.inv_d, lc.eps, wv, rs, rs_lds);
+  if (tr && w == 0 && lane == 0 && tile0 == 0) {
+    tr[1] = wall_clock64();
+    tr[3] = wait_ticks;
   }
 
   // ---- reduction over the seven waves and epilogue, TPC column tiles at a time ----
@@ -549,20 +795,20 @@ __device__ __forceinline__ bool gemm_pass(const StackArgs &a, Wave &wv, lds_t ld
         for (int tt = 0; tt < TPC; ++tt)
           if (c0 + tt < NT) acc[mt][c0 + tt] += red[(buf * RED_TILES + mt * TPC + tt) * 64 + lane];
     };
-    const unsigned q = wv.tree_seq;
+    const unsigned q = wv.st.tree_seq;
     auto signal = [&](unsigned v) {
       if (lane == 0) ctl_write(wv.ctl + 4 * (C_TREE + w), v);
     };
     // ((w0 + w4) + (w2 + w6)) + (w3 + (w1 + w5)); a wave only ever overwrites a buffer it has
     // itself finished reading
     if (w >= 4) { put(w - 4); signal(q + 1); }
-    if (w < 3) { if (!ctl_wait_ge(wv, C_TREE + w + 4, q + 1)) return false; add(w); }
+    if (w < 3) { if (!ctl_wait_ge(wv, C_TREE + w + 4, q + 1)) return wv.st; add(w); }
     if (w == 2) { put(2); signal(q + 2); }
     if (w == 1) { put(1); signal(q + 2); }
-    if (w == 0) { if (!ctl_wait_ge(wv, C_TREE + 2, q + 2)) return false; add(2); }
-    if (w == 3) { if (!ctl_wait_ge(wv, C_TREE + 1, q + 2)) return false; add(1); put(1); signal(q + 3); }
+    if (w == 0) { if (!ctl_wait_ge(wv, C_TREE + 2, q + 2)) return wv.st; add(2); }
+    if (w == 3) { if (!ctl_wait_ge(wv, C_TREE + 1, q + 2)) return wv.st; add(1); put(1); signal(q + 3); }
     if (w == 0) {
-      if (!ctl_wait_ge(wv, C_TREE + 3, q + 3)) return false;
+      if (!ctl_wait_ge(wv, C_TREE + 3, q + 3)) return wv.st;
       add(1);
       // finished tile, row-major: acc[mt][t][i] is (row 16 mt + 4 (lane >> 4) + i, column 16 t + (lane & 15))
       const int q4 = lane >> 4, c16 = lane & 15;
@@ -575,167 +821,56 @@ __device__ __forceinline__ bool gemm_pass(const StackArgs &a, Wave &wv, lds_t ld
             for (int i = 0; i < 4; ++i) tile[(16 * mt + 4 * q4 + i) * LDT + 16 * tt + c16] = acc[mt][c0 + tt][i];
       signal(q + 4);
     }
-    wv.tree_seq = q + 4;
-    if (!ctl_wait_ge(wv, C_TREE + 0, q + 4)) return false;
+    wv.st.tree_seq = q + 4;
+    if (!ctl_wait_ge(wv, C_TREE + 0, q + 4)) return wv.st;
     __atomic_signal_fence(__ATOMIC_SEQ_CST);
-
-    const int tid = w * 64 + lane;
-    const int ntc = (NT - c0) < TPC ? (NT - c0) : TPC;  // column tiles in this chunk
-    const int G = gridDim.x, cu = blockIdx.x;
-    if (io.mode == MODE_QKV) {
-      // A tile holds channels 8j..8j+7 (columns 0..7) and dh/2 + 8j.. (columns 8..15) of one
-      // head: both members of eight RoPE pairs.  One thread per (row, tile).
-      for (int it = tid; it < a.Bp * ntc; it += CONS_THREADS) {
-        const int b = it / ntc, tt = it - b * ntc;
-        const int gt = cu + G * (tile0 + c0 + tt);
-        const int half = a.dh >> 1, spj = a.dh >> 4, grp = a.Hq / a.Hkv;
-        const int hs = gt / spj, j = gt - hs * spj;
-        const float rsf = rs_lds[b];
-        LDS_AS const float *tr = tile + b * LDT + 16 * tt;
-        const float qscale = hs < a.Hq ? 1.0f / sqrtf((float)a.dh) : 1.0f;
-        float y0[8], y1[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          float x0 = tr[k] * rsf, x1 = tr[8 + k] * rsf;
-          if (hs < a.Hq + a.Hkv) {
-            float c = a.cs[((size_t)b * half + 8 * j + k) * 2], sn = a.cs[((size_t)b * half + 8 * j + k) * 2 + 1];
-            y0[k] = (x0 * c - x1 * sn) * qscale;
-            y1[k] = (x1 * c + x0 * sn) * qscale;
-          } else {
-            y0[k] = x0;
-            y1[k] = x1;
-          }
-        }
-        u32x4 lo = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y0[4], y0[5]), pack_bf16(y0[6], y0[7])};
-        u32x4 hi = {pack_bf16(y1[0], y1[1]), pack_bf16(y1[2], y1[3]), pack_bf16(y1[4], y1[5]), pack_bf16(y1[6], y1[7])};
-        const int o_lo = j, o_hi = (half >> 3) + j;  // channel octets of the two pieces
-        if (hs < a.Hq) {
-          __amdgpu_buffer_rsrc_t rqf = rsrc_of(a.qf);
-          int kvh = hs / grp, jq = hs - kvh * grp, rt = jq * MT + (b >> 4);
-          size_t fb = ((size_t)kvh * (grp * MT) + rt) * (a.dh >> 5);
-          st128(rqf, (unsigned)(((fb + (o_lo >> 2)) * 64 + (b & 15) + 16 * (o_lo & 3)) * 16), lo);
-          st128(rqf, (unsigned)(((fb + (o_hi >> 2)) * 64 + (b & 15) + 16 * (o_hi & 3)) * 16), hi);
-        } else if (hs < a.Hq + a.Hkv) {
-          __amdgpu_buffer_rsrc_t rk = rsrc_of(io.Kc);
-          size_t rb = ((size_t)(io.L + b) * a.Hkv + (hs - a.Hq)) * a.dh;
-          st128(rk, (unsigned)((rb + 8 * o_lo) * 2), lo);
-          st128(rk, (unsigned)((rb + 8 * o_hi) * 2), hi);
-        } else {
-          __amdgpu_buffer_rsrc_t rv = rsrc_of(io.Vc);
-          int h = hs - a.Hq - a.Hkv;
-#pragma unroll
-          for (int k = 0; k < 8; ++k) {
-            st16(rv, (unsigned)(v_index(true, io.L + b, h, 8 * j + k, a.Hkv, a.dh) * 2), float_to_bf16(y0[k]));
-            st16(rv, (unsigned)(v_index(true, io.L + b, h, half + 8 * j + k, a.Hkv, a.dh) * 2), float_to_bf16(y1[k]));
-          }
-        }
-      }
-    } else if (io.mode == MODE_RESID) {
-      // x[:, tile columns] += tile; sum of squares of the new values; fragments of x * gain.
-      // Two threads per (row, tile), eight columns each.  This workgroup owns these columns of
-      // x in every layer, so x needs no device-scope accesses.
-      for (int it = tid; it < a.Bp * ntc * 2; it += CONS_THREADS) {
-        const int oct = it & 1, bt = it >> 1;
-        const int b = bt / ntc, tt = bt - b * ntc;
-        const int gt = cu + G * (tile0 + c0 + tt);
-        const int col = 16 * gt + 8 * oct;
-        f32x4 *xp = reinterpret_cast<f32x4 *>(a.x + (size_t)b * a.d + col);
-        LDS_AS const float *tr = tile + b * LDT + 16 * tt + 8 * oct;
-        f32x4 x0 = xp[0], x1 = xp[1];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          x0[i] += tr[i];
-          x1[i] += tr[4 + i];
-        }
-        xp[0] = x0;
-        xp[1] = x1;
-        float sq = 0.f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
-        sq += __shfl_xor(sq, 1, 64);
-        if (io.gain) {
-          if (oct == 0) st32f(rsrc_of(io.rsq_out), (unsigned)(b * a.ncg + gt) * 4, sq);
-          const float *gp = io.gain + col;
-          u32x4 v = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
-                     pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
-          st128(rsrc_of(io.xa_out), frag_piece(col, b, MT), v);
-        }
-      }
-    } else if (io.mode == MODE_GATEUP) {
-      // tile columns: 8 gate channels, then the same 8 channels of up
-      __amdgpu_buffer_rsrc_t rp = rsrc_of(io.act_a);
-      for (int it = tid; it < a.Bp * ntc; it += CONS_THREADS) {
-        const int b = it / ntc, tt = it - b * ntc;
-        const int gt = cu + G * (tile0 + c0 + tt);
-        const float rsf = rs_lds[b];
-        LDS_AS const float *gp = tile + b * LDT + 16 * tt, *up = gp + 8;
-        float act[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          float g = gp[i] * rsf, u = up[i] * rsf;
-          act[i] = g / (1.0f + __expf(-g)) * u;
-        }
-        st128(rp, frag_piece(8 * gt, b, MT),
-              u32x4{pack_bf16(act[0], act[1]), pack_bf16(act[2], act[3]), pack_bf16(act[4], act[5]), pack_bf16(act[6], act[7])});
-      }
-    } else {  // MODE_UNEMBED: arg-max of each row over this chunk's columns, 4 threads per row
-      const int row = tid >> 2, j = tid & 3;
-      Top best{-INFINITY, 0x7fffffff, -INFINITY};
-      if (row < a.Bp)
-        for (int c = j; c < 16 * ntc; c += 4) {
-          int gt = cu + G * (tile0 + c0 + (c >> 4));
-          best = top_merge2(best, Top{tile[row * LDT + c], 16 * gt + (c & 15), -INFINITY});
-        }
-#pragma unroll
-      for (int o = 1; o < 4; o <<= 1) {
-        Top other;
-        other.v1 = __shfl_xor(best.v1, o, 64);
-        other.i1 = __shfl_xor(best.i1, o, 64);
-        other.v2 = __shfl_xor(best.v2, o, 64);
-        best = top_merge2(best, other);
-      }
-      if (j == 0 && row < a.Bp) {
-        __amdgpu_buffer_rsrc_t rp = rsrc_of(io.un_part);
-        unsigned o = (unsigned)(((size_t)(io.part0 + c0 / TPC) * 64 + row) * sizeof(Top));
-        st32f(rp, o, best.v1);
-        __builtin_amdgcn_raw_buffer_store_b32((unsigned)best.i1, rp, o + 4, 0, DEV);
-        st32f(rp, o + 8, best.v2);
-      }
+    if (c0 == 0 && tile0 == 0) tr_mark(tr, wv, 4);
+    {
+      EpiInts e;
+      e.lds0 = lds0;
+      e.mode = uni(p.mode);
+      e.tile_first = tile0 + c0;
+      e.ntc = (NT - c0) < TPC ? (NT - c0) : TPC;
+      e.LDT = LDT;
+      e.part = p.part0 + c0 / TPC;
+      e.tid = w * 64 + lane;
+      if (!(lc.dbg & 8)) gemm_epilogue(e);
     }
     // everyone has finished reading the tile before the buffers are written again
-    if (!cons_barrier(wv)) return false;
+    if (c0 == 0 && tile0 == 0) tr_mark(tr, wv, 5);
+    if (!cons_barrier(wv)) return wv.st;
   }
-  return true;
+  return wv.st;
 }
 
-// All passes of one GEMM for this CU.  sbase: stream index of the GEMM's first fragment.
-// Returns the number of fragments the GEMM occupies in this CU's stream through *used.
+// All passes of one GEMM for this CU.  p.sbase: stream index of the GEMM's first fragment.
 template <int MT>
-__device__ __forceinline__ bool gemm_phase(const StackArgs &a, Wave &wv, lds_t lds, GemmIo io, const GemmDev &g, unsigned sbase,
-                                           bool need_rs) {
+__device__ __forceinline__ WaveState gemm_phase(PassArgs p, WaveState st, const GemmDev &g, unsigned lds0, int w) {
   const int nt = uni(my_tiles(g.ntiles));
-  sbase = uni(sbase);
+  p.KT = g.KT;
   int part = 0;
   for (int t0 = 0; t0 < nt; t0 += g.ntp) {
     const int n = nt - t0 < g.ntp ? nt - t0 : g.ntp;
-    io.part0 = part;
-    bool ok;
+    p.part0 = part;
+    p.tile0 = t0;
+    lds_put(lds0 + LDS_ARGS + 128 * w, p);  // every lane stores the same values
     switch (n) {
-      case 1: ok = gemm_pass<MT, 1>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      case 2: ok = gemm_pass<MT, 2>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      case 3: ok = gemm_pass<MT, 3>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      case 4: ok = gemm_pass<MT, 4>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      case 5: ok = gemm_pass<MT, 5>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      case 6: ok = gemm_pass<MT, 6>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      case 7: ok = gemm_pass<MT, 7>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
-      default: ok = gemm_pass<MT, 8>(a, wv, lds, io, g.KT, sbase, t0, need_rs); break;
+      case 1: st = gemm_pass<MT, 1>(lds0, st); break;
+      case 2: st = gemm_pass<MT, 2>(lds0, st); break;
+      case 3: st = gemm_pass<MT, 3>(lds0, st); break;
+      case 4: st = gemm_pass<MT, 4>(lds0, st); break;
+      case 5: st = gemm_pass<MT, 5>(lds0, st); break;
+      case 6: st = gemm_pass<MT, 6>(lds0, st); break;
+      case 7: st = gemm_pass<MT, 7>(lds0, st); break;
+      default: st = gemm_pass<MT, 8>(lds0, st); break;
     }
-    if (!ok) return false;
-    sbase += (unsigned)(n * g.KT);
+    st.ok = uni(st.ok);
+    if (!st.ok) return st;
+    p.sbase += (unsigned)(n * g.KT);
     constexpr int tpc_max = RED_TILES / MT;
     part += (n + tpc_max - 1) / tpc_max;
   }
-  return true;
+  return st;
 }
 
 // ---- first operand of a launch: norm statistics and fragments of x * gain ----------------------
@@ -783,15 +918,39 @@ __device__ __forceinline__ void rope_table_phase(const StackArgs &a, const Wave 
 //   S^T = K Q^T      A = K tile [16 keys x 32 dh],   B = q fragment        -> lane: 4 keys of one q-row
 //   O^T = V^T P^T    A = V^T tile [16 dh x 32 keys], B = p of 2 key tiles  -> lane: 4 channels of one q-row
 // V is stored key-blocked (v_index) so that the V^T tile is one 128-bit load per lane.
+struct AttArgs {
+  const uint16_t *Kc, *Vc;
+  uint16_t *attn_out;
+  const uint64_t *vis;
+  unsigned lds0;
+  unsigned long long *tr;
+};
+
 template <int DH>
-__device__ __forceinline__ bool attention_phase(const StackArgs &a, Wave &wv, lds_t lds, const uint16_t *Kc, const uint16_t *Vc,
-                                                uint16_t *attn_out, int L) {
+__device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveState st_in) {
   constexpr int KT = DH / 32, DT = DH / 16;
   static_assert(DT <= RED_TILES, "one wave's output must fit a reduction buffer");
-  __amdgpu_buffer_rsrc_t rk = rsrc_of(Kc), rv = rsrc_of(Vc), rqf = rsrc_of(a.qf), ra = rsrc_of(attn_out);
-  LDS_AS f32x4 *red = (LDS_AS f32x4 *)(lds + LDS_RED);
-  LDS_AS float *mlb = (LDS_AS float *)(lds + LDS_ML);
-  const int w = uni(wv.w), lane = wv.lane, q4 = lane >> 4, c16 = lane & 15;
+  struct {
+    int Bp, MT, Hq, Hkv;
+    const uint64_t *vis;
+  } a;
+  const unsigned lds0 = uni(p.lds0);
+  const LaunchConst lc = launch_const(lds0);
+  a.Bp = lc.Bp; a.MT = lc.MT; a.Hq = lc.Hq; a.Hkv = lc.Hkv; a.vis = uni_ptr(p.vis);
+  const int L = lc.L;
+  unsigned long long *tr = uni_ptr(p.tr);
+  Wave wv;
+  wv.w = uni((int)(threadIdx.x >> 6));
+  wv.lane = threadIdx.x & 63;
+  wv.ctl = lds0 + LDS_CTL;
+  wv.st.cbar_seq = uni(st_in.cbar_seq);
+  wv.st.tree_seq = uni(st_in.tree_seq);
+  wv.st.seen = uni(st_in.seen);
+  wv.st.ok = 1;
+  __amdgpu_buffer_rsrc_t rk = rsrc_of(p.Kc), rv = rsrc_of(p.Vc), rqf = rsrc_of(lc.qf), ra = rsrc_of(p.attn_out);
+  LDS_AS f32x4 *red = (LDS_AS f32x4 *)(uintptr_t)(lds0 + LDS_RED);
+  LDS_AS float *mlb = (LDS_AS float *)(uintptr_t)(lds0 + LDS_ML);
+  const int w = wv.w, lane = wv.lane, q4 = lane >> 4, c16 = lane & 15;
   const int g = a.Hq / a.Hkv, n_rt = g * a.MT;
   const int total = L + a.Bp, nkb = (total + 31) >> 5;
   for (int u = blockIdx.x; u < a.Hkv * n_rt; u += gridDim.x) {
@@ -819,6 +978,10 @@ __device__ __forceinline__ bool attention_phase(const StackArgs &a, Wave &wv, ld
       for (int dt = 0; dt < DT; ++dt) pv[dt] = ld128(rv, v_off + dt * 16 * 32 * 2);
     };
     load_kv(w, nka, nkbv, nvt);
+    if (u == blockIdx.x) {
+      wait_vmcnt<0>();
+      tr_mark(tr, wv, 9);
+    }
     for (int kb = w; kb < nkb; kb += NCW) {
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
@@ -867,6 +1030,7 @@ __device__ __forceinline__ bool attention_phase(const StackArgs &a, Wave &wv, ld
         o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[dt]), pb, o[dt], 0, 0, 0);
       }
     }
+    if (u == blockIdx.x) tr_mark(tr, wv, 10);
     // merge the seven partial results: ((w0 + w4) + (w2 + w6)) + (w3 + (w1 + w5))
     auto put = [&](int buf) {
 #pragma unroll
@@ -883,19 +1047,20 @@ __device__ __forceinline__ bool attention_phase(const StackArgs &a, Wave &wv, ld
       for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * ca + red[(buf * RED_TILES + dt) * 64 + lane] * cb;
       m_run = m_new;
     };
-    const unsigned qs = wv.tree_seq;
+    const unsigned qs = wv.st.tree_seq;
     auto signal = [&](unsigned v) {
       if (lane == 0) ctl_write(wv.ctl + 4 * (C_TREE + w), v);
     };
     if (w >= 4) { put(w - 4); signal(qs + 1); }
-    if (w < 3) { if (!ctl_wait_ge(wv, C_TREE + w + 4, qs + 1)) return false; merge(w); }
+    if (w < 3) { if (!ctl_wait_ge(wv, C_TREE + w + 4, qs + 1)) return wv.st; merge(w); }
     if (w == 2) { put(2); signal(qs + 2); }
     if (w == 1) { put(1); signal(qs + 2); }
-    if (w == 0) { if (!ctl_wait_ge(wv, C_TREE + 2, qs + 2)) return false; merge(2); }
-    if (w == 3) { if (!ctl_wait_ge(wv, C_TREE + 1, qs + 2)) return false; merge(1); put(1); signal(qs + 3); }
+    if (w == 0) { if (!ctl_wait_ge(wv, C_TREE + 2, qs + 2)) return wv.st; merge(2); }
+    if (w == 3) { if (!ctl_wait_ge(wv, C_TREE + 1, qs + 2)) return wv.st; merge(1); put(1); signal(qs + 3); }
     if (w == 0) {
-      if (!ctl_wait_ge(wv, C_TREE + 3, qs + 3)) return false;
+      if (!ctl_wait_ge(wv, C_TREE + 3, qs + 3)) return wv.st;
       merge(1);
+      if (u == blockIdx.x) tr_mark(tr, wv, 11);
       // o[dt][i] = O^T[channel 16 dt + 4 q4 + i][q-row c16]: four channels = half a 16-byte piece
       if (b < a.Bp) {
         const float inv = 1.0f / l_run;
@@ -909,11 +1074,11 @@ __device__ __forceinline__ bool attention_phase(const StackArgs &a, Wave &wv, ld
       }
       signal(qs + 4);
     }
-    wv.tree_seq = qs + 4;
+    wv.st.tree_seq = qs + 4;
     // the buffers are free again once wave 0 has read the last of them
-    if (!ctl_wait_ge(wv, C_TREE + 0, qs + 4)) return false;
+    if (!ctl_wait_ge(wv, C_TREE + 0, qs + 4)) return wv.st;
   }
-  return true;
+  return wv.st;
 }
 
 // Arg-max over the partial records; logits carry the row's norm factor from here on.
@@ -962,6 +1127,11 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
     return;
   }
   if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + LDS_CTL))[threadIdx.x] = 0u;
+  if (threadIdx.x == 64) {
+    LDS_AS LaunchConst *c = (LDS_AS LaunchConst *)(lds + LDS_CONST);
+    c->Bp = a.Bp; c->MT = MT; c->d = a.d; c->ncg = a.ncg; c->Hq = a.Hq; c->Hkv = a.Hkv; c->dh = a.dh; c->L = L; c->dbg = a.dbg;
+    c->inv_d = a.inv_d; c->eps = a.eps; c->x = a.x; c->cs = a.cs; c->qf = a.qf;
+  }
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const unsigned ctl = (unsigned)(uintptr_t)(lds + LDS_CTL);
@@ -973,7 +1143,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   const unsigned f_un = ((unsigned)(my_tiles(a.un.ntiles) * a.un.KT) + CHUNK - 1) / CHUNK * CHUNK;
 
   if (wave == NCW) {
-    unsigned long long *st = a.trace ? a.trace + 4 * a.trace_phases + 8 * blockIdx.x : nullptr;
+    unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + 8 * blockIdx.x : nullptr;
     if (a.mode == 0) producer(a, ctl, lds + LDS_RING, (unsigned)a.lb, (unsigned)(a.le - a.lb), f_layer, a.seg_frags, st);
     else producer(a, ctl, lds + LDS_RING, 0u, 1u, f_un, a.seg_frags, st);
     return;
@@ -983,21 +1153,24 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   wv.ctl = ctl;
   wv.w = wave;
   wv.lane = threadIdx.x & 63;
-  wv.cbar_seq = 0;
-  wv.tree_seq = 0;
-  wv.seen = 0;
-  wv.wait_ticks = 0;
-  wv.dead = false;
+  wv.st.cbar_seq = 0;
+  wv.st.tree_seq = 0;
+  wv.st.seen = 0;
+  wv.st.ok = 1;
   unsigned epoch = a.epoch0;
+  const unsigned lds0 = (unsigned)(uintptr_t)lds;
 
   // Phase list.  Layer stack: PREP, then per layer QKV, ATT, O, GU, DOWN.  Unembedding: PREP,
-  // GEMM, FINAL.  One loop with one GEMM call site keeps the kernel's code small.
+  // GEMM, FINAL.  The GEMM passes and the attention are functions of their own; this loop only
+  // sets up their arguments and runs the grid barrier between phases.
   const int n_phases = a.mode == 1 ? 3 : 1 + 5 * (a.le - a.lb);
   unsigned sbase = 0;
+  unsigned long long *tr = nullptr;  // timeline slots of the current phase (workgroup 0 only)
   for (int ph = 0; ph < n_phases; ++ph) {
-    if (ph > 0 && !grid_sync(a, wv, ++epoch)) return;
-    trace_mark(a, wv, ph, 0);
-    wv.trace_phase = ph;
+    if (ph > 0 && !grid_sync(a, wv, ++epoch, tr)) return;
+    tr = (a.trace && blockIdx.x == 0 && ph < a.trace_phases) ? a.trace + TRACE_SLOTS * ph : nullptr;
+    tr_mark(tr, wv, 0);
+    if (tr && wv.w == 0 && wv.lane == 0) tr[12] = clock64();  // shader clock, to report the running frequency
     const int sub = a.mode == 1 ? (ph == 0 ? 0 : ph == 1 ? 6 : 7) : (ph == 0 ? 0 : 1 + (ph - 1) % 5);
     const int layer = a.mode == 1 ? 0 : (ph == 0 ? a.lb : a.lb + (ph - 1) / 5);
     uint16_t *Kc = a.K + (size_t)layer * a.layer_elems, *Vc = a.V + (size_t)layer * a.layer_elems;
@@ -1006,9 +1179,10 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
     uint16_t *xa0 = a.xa + (size_t)(2 * layer) * a.xa_stride, *xa1 = xa0 + a.xa_stride;
     float *rsq0 = a.rsq + (size_t)(2 * layer) * a.rsq_stride, *rsq1 = rsq0 + a.rsq_stride;
     uint16_t *attn_l = a.attn_a + (size_t)layer * a.attn_stride, *act_l = a.act_a + (size_t)layer * a.act_stride;
-    GemmIo io{};
-    const GemmDev *g = nullptr;
-    bool need_rs = false;
+    PassArgs p{};
+    p.tr = tr;
+    GemmDev g{};
+    bool have_g = false;
     unsigned frags = 0;
     switch (sub) {
       case 0:  // first operand of the launch
@@ -1020,27 +1194,31 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
         }
         break;
       case 1:
-        io.A = xa0; io.mode = MODE_QKV; io.rsq_in = rsq0; io.Kc = Kc; io.Vc = Vc; io.L = L;
-        g = &a.qkv; need_rs = true; frags = f_qkv;
+        p.A = xa0; p.mode = MODE_QKV; p.rsq_in = rsq0; p.q.Kc = Kc; p.q.Vc = Vc;
+        g = a.qkv; have_g = true; frags = f_qkv;
         break;
-      case 2:
-        if (a.dh == 128) { if (!attention_phase<128>(a, wv, lds, Kc, Vc, attn_l, L)) return; }
-        else { if (!attention_phase<64>(a, wv, lds, Kc, Vc, attn_l, L)) return; }
+      case 2: {
+        AttArgs t;
+        t.Kc = Kc; t.Vc = Vc; t.attn_out = attn_l; t.vis = a.vis; t.lds0 = lds0; t.tr = tr;
+        wv.st = a.dh == 128 ? attention_phase<128>(t, wv.st) : attention_phase<64>(t, wv.st);
+        wv.st.ok = uni(wv.st.ok);
+        if (!wv.st.ok) return;
         break;
+      }
       case 3:
-        io.A = attn_l; io.mode = MODE_RESID; io.gain = a.gains[layer].g_mlp; io.xa_out = xa1; io.rsq_out = rsq1;
-        g = &a.o; frags = f_o;
+        p.A = attn_l; p.mode = MODE_RESID; p.q.gain = a.gains[layer].g_mlp; p.q.xa_out = xa1; p.q.rsq_out = rsq1;
+        g = a.o; have_g = true; frags = f_o;
         break;
       case 4:
-        io.A = xa1; io.mode = MODE_GATEUP; io.rsq_in = rsq1; io.act_a = act_l;
-        g = &a.gu; need_rs = true; frags = f_gu;
+        p.A = xa1; p.mode = MODE_GATEUP; p.rsq_in = rsq1; p.q.act_a = act_l;
+        g = a.gu; have_g = true; frags = f_gu;
         break;
       case 5:
         // the fragments feed the next layer's QKV GEMM; the last layer of the call needs none
-        io.A = act_l; io.mode = MODE_RESID;
-        io.gain = layer + 1 < a.le ? a.gains[layer + 1].g_attn : nullptr;
-        io.xa_out = xa0 + 2 * a.xa_stride; io.rsq_out = rsq0 + 2 * a.rsq_stride;
-        g = &a.down; frags = f_layer - f_qkv - f_o - f_gu;  // with the layer's padding
+        p.A = act_l; p.mode = MODE_RESID;
+        p.q.gain = layer + 1 < a.le ? a.gains[layer + 1].g_attn : nullptr;
+        p.q.xa_out = xa0 + 2 * a.xa_stride; p.q.rsq_out = rsq0 + 2 * a.rsq_stride;
+        g = a.down; have_g = true; frags = f_layer - f_qkv - f_o - f_gu;  // with the layer's padding
         break;
       case 6: {
         // every CU writes all of its partial records: the ones it has no tiles for stay empty
@@ -1054,19 +1232,21 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
           __builtin_amdgcn_raw_buffer_store_b32(0x7fffffffu, rp, o + 4, 0, DEV);
           st32f(rp, o + 8, -INFINITY);
         }
-        io.A = a.xa; io.mode = MODE_UNEMBED; io.un_part = a.un_part + (size_t)blockIdx.x * a.un_parts_per_cu * 64;
-        g = &a.un; frags = f_un;
+        p.A = a.xa; p.mode = MODE_UNEMBED; p.q.un_part = a.un_part + (size_t)blockIdx.x * a.un_parts_per_cu * 64;
+        g = a.un; have_g = true; frags = f_un;
         break;
       }
       default:
         unembed_final_phase(a, wv);
         break;
     }
-    if (g) {
-      if (!gemm_phase<MT>(a, wv, lds, io, *g, sbase, need_rs)) return;
+    if (have_g) {
+      p.sbase = sbase;
+      wv.st = gemm_phase<MT>(p, wv.st, g, lds0, wv.w);
+      if (!wv.st.ok) return;
       sbase += frags;
     }
-    trace_mark(a, wv, ph, 2);
+    tr_mark(tr, wv, 2);
   }
 }
 
