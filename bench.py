@@ -107,6 +107,20 @@ def cpu_baseline(shape):
     }
 
 
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "layer_stack_config2_pmc.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +128,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=N_LAYERS, help=argparse.SUPPRESS)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch a 1 GiB copy kernel (calib_copy) before the timed steps: a dispatch of known "
+                         "traffic for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -143,6 +160,13 @@ def main():
     for _ in range(args.warmup):
         eng.step(emitted, budget)
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            B.la_profile_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     st0 = B.read_state(eng.state)
 
     dominant = "layer_stack"   # the persistent kernel that runs all layers of the step
@@ -206,7 +230,7 @@ def main():
         "kernel_ms_per_step": per_step,
         "roofline": {
             "bound": "hbm", "kernel": dominant, "achieved": round(dom_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-            "frac": round(dom_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+            "frac": round(dom_gbps / PEAK_HBM_GBPS, 4), "traffic": measured_traffic(),
             "bytes_per_launch": dom_bytes, "launches": launches, "avg_launch_ms": round(dom_ms, 5),
         },
     }

@@ -199,6 +199,10 @@ int la_profile_enable(int on);
 /* Restricts the bracketing to kernels of one name (NULL or "" = all kernels again). */
 int la_profile_select(const char *kernel_name);
 int la_profile_read(la_profile_entry *out_host, int cap);
+/* A plain copy kernel (launch name "calib_copy") that reads `bytes` from src and writes them to
+ * dst (device pointers, 16-byte aligned, bytes a multiple of 16): a dispatch of known HBM
+ * traffic, against which hardware byte counters read for the other kernels can be scaled. */
+int la_profile_copy(void *dst, const void *src, size_t bytes, void *stream);
 
 const char *la_last_error(void);
 

@@ -61,7 +61,7 @@ EXPORTS = [
     "la_init_model", "la_model_set_layer", "la_free_model", "la_kv_alloc", "la_kv_set_len", "la_kv_get_len",
     "la_kv_fill", "la_kv_read", "la_free_kv", "la_embed", "la_forward_layers", "la_unembed_argmax",
     "la_pool_alloc", "la_free_pool", "la_state_init", "la_ngram_accept", "la_lookahead_layout",
-    "la_profile_enable", "la_profile_select", "la_profile_read", "la_last_error",
+    "la_profile_enable", "la_profile_select", "la_profile_read", "la_profile_copy", "la_last_error",
 ]
 
 
@@ -93,6 +93,7 @@ def _load():
         "la_profile_enable": (i32, [i32]),
         "la_profile_select": (i32, [C.c_char_p]),
         "la_profile_read": (i32, [C.POINTER(la_profile_entry), i32]),
+        "la_profile_copy": (i32, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
         "la_last_error": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -247,6 +248,10 @@ def la_profile_read(cap=64):
     buf = (la_profile_entry * cap)()
     n = lib.la_profile_read(buf, cap)
     return {buf[i].name.decode(): (buf[i].launches, buf[i].total_ms) for i in range(n)}
+
+
+def la_profile_copy(dst: torch.Tensor, src: torch.Tensor):
+    _check(lib.la_profile_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream()))
 
 
 # ---- state helpers (views of the published struct layout) ------------------------------

@@ -81,6 +81,10 @@ __global__ void kv_copy_kernel(T *Kl, T *Vl, T *k, T *v, int row0, int n, int Hk
 
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { *p = v; }
 
+__global__ void calib_copy_kernel(uint4 *dst, const uint4 *src, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 }  // namespace la
 
 using namespace la;
@@ -123,6 +127,16 @@ extern "C" int la_profile_read(la_profile_entry *out, int cap) {
   }
   g_prof.clear();
   return n;
+}
+
+extern "C" int la_profile_copy(void *dst, const void *src, size_t bytes, void *stream) {
+  LA_REQUIRE(dst && src && bytes % 16 == 0 && ((uintptr_t)dst | (uintptr_t)src) % 16 == 0, LA_EINVAL,
+             "la_profile_copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope ps("calib_copy", s);
+  calib_copy_kernel<<<2048, 256, 0, s>>>((uint4 *)dst, (const uint4 *)src, bytes / 16);
+  LA_HIP(hipGetLastError());
+  return LA_OK;
 }
 
 static void *dev_alloc(size_t bytes) {
