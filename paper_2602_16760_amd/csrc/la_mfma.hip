@@ -327,8 +327,8 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       const unsigned long long t0 = h[S * q];
       auto rel = [&](int k) { return h[S * q + k] > t0 ? (h[S * q + k] - t0) * 0.01 : -1.0; };
       double since_prev = q > 0 ? (t0 - h[S * (q - 1) + 2]) * 0.01 : 0.0;
-      fprintf(stderr, "[la trace]   phase %2d: +%5.2f | pass entry %5.2f loop start %5.2f 2nd batch %5.2f | k-loop end %6.2f (waited for weights %6.2f) tile %6.2f epilogue %6.2f | attn: loads %6.2f loop %6.2f merged %6.2f | "
-              "work end %6.2f | barrier: stores %6.2f waves %6.2f released %6.2f\n", q, since_prev, rel(13), rel(14), rel(15), rel(1), h[S * q + 1] > t0 ? h[S * q + 3] * 0.01 : -1.0,
+      fprintf(stderr, "[la trace]   phase %2d: +%5.2f | k-loop end %6.2f (waited for weights %6.2f) tile %6.2f epilogue %6.2f | attn: loads %6.2f loop %6.2f merged %6.2f | "
+              "work end %6.2f | barrier: stores %6.2f waves %6.2f released %6.2f\n", q, since_prev, rel(1), h[S * q + 1] > t0 ? h[S * q + 3] * 0.01 : -1.0,
               rel(4), rel(5), rel(9), rel(10), rel(11), rel(2), rel(6), rel(7), rel(8));
     }
     if (np > 1 && h[S * (np - 1)] > h[0])

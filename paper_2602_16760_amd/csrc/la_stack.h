@@ -55,8 +55,8 @@ constexpr int WG_THREADS = 512;
 constexpr int NCW = 7;                     // consumer waves 0..6; wave 7 streams the weights
 constexpr int CONS_THREADS = NCW * 64;
 constexpr int NSLOT = 128;                 // ring slots of 1 KB (a power of two)
-constexpr int CHUNK = 4;                   // fragments the producer issues back to back
-constexpr int FLIGHT = 12;                 // chunks in flight: 48 loads, the counter holds 63
+constexpr int CHUNK = 8;                   // fragments the producer issues back to back
+constexpr int FLIGHT = 7;                  // chunks in flight: 56 loads, the counter holds 63
 constexpr int RED_TILES = 8;               // 1 KB accumulator tiles per tree-reduction buffer
 constexpr int MAX_NT = 8;                  // column tiles of one pass
 constexpr int MAX_MT = LA_MAX_ROWS / 16;
@@ -85,6 +85,7 @@ constexpr int C_DEAD = 1;     // a wait timed out: every wave leaves the kernel
 constexpr int C_CBAR = 2;     // arrivals at the consumer-wave barrier
 constexpr int C_GPASS = 3;    // last grid-barrier epoch seen released
 constexpr int C_PROG = 8;     // [8..14] per consumer wave: first stream fragment it still needs
+constexpr int C_SPARE = 7;   // written, never read
 constexpr int C_TREE = 16;    // [16..22] per consumer wave: hand-off sequence number
 
 struct Top {  // running arg-max of one row: best value, its index, runner-up value
@@ -371,42 +372,64 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
   unsigned next = 0, landed = 0, inflight = 0, free_until = NSLOT;
   unsigned seg_off = first_seg * seg_stride, f_in_seg = 0;  // memory position of fragment `next`
   unsigned polls = 0, full_events = 0;
-  unsigned long long t_drain = 0, t_poll = 0, t_flight = 0;
+  unsigned long long t_wait = 0, t_poll = 0;
   const bool tr = stats != nullptr;
   const unsigned long long t_begin = tr ? wall_clock64() : 0ull;
   if (a.dbg & 1) {
     ctl_write(ctl + 4 * C_LANDED, total);
     return;
   }
+  // the oldest chunk in flight has landed once at most (inflight - 1) chunks are outstanding
+  auto retire_oldest = [&]() {
+    switch (inflight) {
+      case 1: wait_vmcnt<0 * CHUNK>(); break;
+      case 2: wait_vmcnt<1 * CHUNK>(); break;
+      case 3: wait_vmcnt<2 * CHUNK>(); break;
+      case 4: wait_vmcnt<3 * CHUNK>(); break;
+      case 5: wait_vmcnt<4 * CHUNK>(); break;
+      case 6: wait_vmcnt<5 * CHUNK>(); break;
+      default: wait_vmcnt<6 * CHUNK>(); break;
+    }
+    static_assert(FLIGHT == 7 && FLIGHT * CHUNK <= 63, "one case per number of chunks in flight");
+    landed += CHUNK;
+    ctl_write(ctl + 4 * C_LANDED, landed < total ? landed : total);
+    --inflight;
+  };
+  auto read_space = [&]() {
+    const unsigned c = ctl_read_lanes(ctl + 4 * (C_PROG + (lane < NCW ? lane : 0)));
+    unsigned m = (unsigned)__builtin_amdgcn_readlane((int)c, 0);
+#pragma unroll
+    for (int k = 1; k < NCW; ++k) m = min(m, (unsigned)__builtin_amdgcn_readlane((int)c, k));
+    free_until = m + NSLOT;
+  };
+  unsigned idle_spins = 0;
   while (next < total) {
     if (next + CHUNK > free_until) {
-      // ring full: publish everything in flight, then poll the consumers
-      unsigned long long t0 = tr ? wall_clock64() : 0ull;
-      if (inflight) {
-        wait_vmcnt<0>();
-        landed = next < total ? next : total;
-        ctl_write(ctl + 4 * C_LANDED, landed);
-        inflight = 0;
-      }
-      ++full_events;
-      unsigned long long t1 = tr ? wall_clock64() : 0ull;
-      t_drain += t1 - t0;
-      unsigned spins = 0;
-      for (;;) {
-        unsigned c = ctl_read_lanes(ctl + 4 * (C_PROG + (lane < NCW ? lane : 0)));
-#pragma unroll
-        for (int o = 1; o < 8; o <<= 1) c = min(c, (unsigned)__shfl_xor((int)c, o, 64));
-        c = __builtin_amdgcn_readfirstlane(c);
-        free_until = c + NSLOT;
-        if (next + CHUNK <= free_until) break;
-        __builtin_amdgcn_s_sleep(1);
-        ++polls;
-        if ((++spins & 255u) == 0 && (ctl_read(ctl + 4 * C_DEAD) != 0 || spins > SPIN_LDS)) {
-          ctl_write(ctl + 4 * C_DEAD, 1u);
-          return;
+      read_space();
+      if (next + CHUNK > free_until) {
+        // Ring full.  Chunks in flight keep landing meanwhile: retire them one at a time (the
+        // consumers may be waiting for exactly those), and look for space again after each.
+        if (inflight) {
+          const unsigned long long t0 = tr ? wall_clock64() : 0ull;
+          retire_oldest();
+          if (tr) t_wait += wall_clock64() - t0;
+          continue;
         }
+        const unsigned long long t0 = tr ? wall_clock64() : 0ull;
+        ++full_events;
+        for (;;) {
+          __builtin_amdgcn_s_sleep(1);
+          ++polls;
+          read_space();
+          if (next + CHUNK <= free_until) break;
+          if ((++idle_spins & 255u) == 0 && (ctl_read(ctl + 4 * C_DEAD) != 0 || idle_spins > SPIN_LDS)) {
+            ctl_write(ctl + 4 * C_DEAD, 1u);
+            return;
+          }
+        }
+        idle_spins = 0;
+        if (tr) t_poll += wall_clock64() - t0;
       }
-      if (tr) t_poll += wall_clock64() - t1;
     }
     {
       // a chunk is contiguous in memory and in the ring (segments are padded to whole chunks):
@@ -414,11 +437,17 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
       LDS_AS void *dst = (LDS_AS void *)(ring + (next & (NSLOT - 1)) * 1024);
       const unsigned soff = (seg_off + f_in_seg) * 1024u;
       const unsigned vo = (unsigned)lane * 16u;
-      static_assert(CHUNK == 4, "the chunk is unrolled by hand");
+      static_assert(CHUNK == 8, "the chunk is unrolled by hand");
+      // (the instruction offset reaches 4095: two groups of four)
+      LDS_AS void *dst2 = (LDS_AS void *)(ring + (next & (NSLOT - 1)) * 1024 + 4096);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 0, NT_HINT);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 1024, NT_HINT);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 2048, NT_HINT);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, vo, soff, 3072, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst2, 16, vo, soff + 4096u, 0, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst2, 16, vo, soff + 4096u, 1024, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst2, 16, vo, soff + 4096u, 2048, NT_HINT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst2, 16, vo, soff + 4096u, 3072, NT_HINT);
       f_in_seg += CHUNK;
       if (f_in_seg == seg_used) {
         f_in_seg = 0;
@@ -427,22 +456,19 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
     }
     next += CHUNK;
     if (++inflight == FLIGHT) {
-      unsigned long long t0 = tr ? wall_clock64() : 0ull;
-      wait_vmcnt<(FLIGHT - 1) * CHUNK>();
-      if (tr) t_flight += wall_clock64() - t0;
-      landed += CHUNK;
-      ctl_write(ctl + 4 * C_LANDED, landed);
-      --inflight;
+      const unsigned long long t0 = tr ? wall_clock64() : 0ull;
+      retire_oldest();
+      if (tr) t_wait += wall_clock64() - t0;
     }
   }
-  wait_vmcnt<0>();
+  while (inflight) retire_oldest();
   ctl_write(ctl + 4 * C_LANDED, total);
   if (stats && lane == 0) {
     stats[0] = polls;
     stats[1] = full_events;
-    stats[2] = t_drain;
+    stats[2] = 0;
     stats[3] = t_poll;
-    stats[4] = t_flight;
+    stats[4] = t_wait;
     stats[5] = wall_clock64() - t_begin;
   }
 }
@@ -450,13 +476,11 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
 // ---- GEMM pass (consumer waves) --------------------------------------------------------------
 template <int MT, int NT>
 struct Depth {  // k-tiles per batch of a wave = depth of its activation-operand prefetch
-  // registers: DA operand fragments per row tile beside the accumulators and one k-tile of weights
-  static constexpr int by_regs = (200 - 4 * MT * NT - 4 * NT) / (4 * MT);
-  // ring: the batch of the last wave (k-tiles 6, 13, ..) must fit the ring together with what the
-  // first wave still holds: (6 + 7 (DA - 1) + 1) NT <= NSLOT - CHUNK
-  static constexpr int by_ring = ((NSLOT - CHUNK) / NT - NCW) / NCW + 1;
-  static constexpr int m = by_regs < by_ring ? by_regs : by_ring;
-  static constexpr int value = m < 1 ? 1 : (m > 12 ? 12 : m);
+  // A wave waits for the weights of its whole batch before it starts, which keeps (DA - 1) 7 NT
+  // ring slots from being refilled meanwhile: deep batches only where the k-tiles are small and
+  // the operand latency (about six k-tiles of a wave at full stream rate) would show otherwise.
+  static constexpr int value = NT == 1 ? 6 : NT == 2 ? 4 : NT == 3 ? 3 : NT == 4 ? 2 : 1;
+  static_assert((NCW - 1 + NCW * (value - 1) + 1) * NT <= NSLOT - CHUNK, "the last wave's batch must fit the ring");
 };
 
 // Row factors rsqrt(mean(x^2) + eps) of the block's rows into LDS: wave w takes rows w, w+7, ...
@@ -697,7 +721,9 @@ __device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveS
   const unsigned voff = lane * 16;
   const int nk = KT > w ? (KT - w + NCW - 1) / NCW : 0;  // this wave's k-tiles: w, w + 7, ...
   unsigned long long wait_ticks = 0;
-  if (tile0 == 0) tr_mark(tr, wv, 13);
+  // (no timeline marks between here and the end of the k-loop: a conditional store among the
+  // operand loads makes the number of outstanding memory operations path-dependent, and the
+  // compiler then waits for all of them at every use)
 
   u32x4 rA[DA][MT];
   auto load_a = [&](int slot, int i) {
@@ -722,9 +748,7 @@ __device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveS
   // requests the operand of the slot's next turn, so the operand prefetch is a full batch deep.
   // A slot beyond the wave's last k-tile multiplies zeros and loads out of range (nothing moves).
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-  if (tile0 == 0) tr_mark(tr, wv, 14);
   for (int i0 = 0; i0 < nk; i0 += DA) {
-    if (tile0 == 0 && i0 == DA) tr_mark(tr, wv, 15);
     const int last = (i0 + DA < nk ? i0 + DA : nk) - 1;  // the batch's last valid k-tile of this wave
     const unsigned need = sbase + (unsigned)(w + NCW * last + 1) * NT;
     if ((int)(wv.st.seen - need) < 0) {
@@ -760,14 +784,19 @@ __device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveS
         for (int t = 0; t < NT; ++t)
           acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rA[s][mt]),
                                                                 __builtin_bit_cast(bf16x8, rW[t]), acc[mt][t], 0, 0, 0);
+      // this k-tile's reads are in the LDS queue before the write below: when the producer sees
+      // the new value, the slots have been read (LDS traffic does not disturb the load counting)
+      // Written by every lane, and to a spare word for a slot beyond the last k-tile: a branch
+      // here would split the batch into blocks and cost the precise load counting.
+      {
+        const unsigned nxt = i + 1 < nk ? kt + NCW : (unsigned)KT;
+        // (a plain volatile store between compiler fences rather than the inline-assembly
+        // accessor: inline assembly inside the batch also costs the precise load counting)
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+        *(volatile LDS_AS unsigned *)(uintptr_t)(wv.ctl + 4 * (valid ? C_PROG + w : C_SPARE)) = sbase + nxt * NT;
+        __atomic_signal_fence(__ATOMIC_SEQ_CST);
+      }
       load_a(s, i + DA);
-    }
-    // the batch's reads are in the LDS queue before this write: when the producer sees the new
-    // value, the slots have been read
-    {
-      const int nxt_i = i0 + DA;
-      const unsigned nxt = nxt_i < nk ? (unsigned)(w + NCW * nxt_i) : (unsigned)KT;
-      if (lane == 0) ctl_write(wv.ctl + 4 * (C_PROG + w), sbase + nxt * NT);
     }
   }
   // nothing of this pass is needed any more (also covers a wave that had no k-tile)
