@@ -187,7 +187,7 @@ int mfma_create(la_model *m) {
   f->seg_frags = (unsigned)(f->p_qkv.nt_max * f->p_qkv.KT + f->p_o.nt_max * f->p_o.KT + f->p_gu.nt_max * f->p_gu.KT +
                             f->p_down.nt_max * f->p_down.KT);
   f->seg_frags = (f->seg_frags + CHUNK - 1) / CHUNK * CHUNK;  // the producer moves whole chunks
-  f->cu_bytes = (size_t)d.n_layers * f->seg_frags * 1024;
+  f->cu_bytes = (size_t)d.n_layers * f->seg_frags * 1024 + (size_t)env_int("LA_CU_PAD", 0) / 256 * 256;
   LA_REQUIRE(f->cu_bytes < ((size_t)1 << 31), LA_EINVAL, "one CU's weight stream exceeds 2 GiB");
   f->ucu_bytes = (size_t)(((size_t)f->p_un.nt_max * f->p_un.KT + CHUNK - 1) / CHUNK * CHUNK) * 1024;
   LA_REQUIRE(f->ucu_bytes < ((size_t)1 << 31), LA_EINVAL, "one CU's unembedding stream exceeds 2 GiB");
@@ -220,9 +220,9 @@ int mfma_create(la_model *m) {
   LA_HIP(hipMemset(f->zero_len, 0, 8));
   if (env_int("LA_TRACE", 0)) {
     f->trace_phases = 2 + 5 * d.n_layers;
-    f->trace = (unsigned long long *)dalloc(((size_t)TRACE_SLOTS * f->trace_phases + 8 * f->n_wgs) * 8);
+    f->trace = (unsigned long long *)dalloc(((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs) * 8);
     LA_REQUIRE(f->trace != nullptr, LA_ENOMEM, "device allocation failed");
-    LA_HIP(hipMemset(f->trace, 0, ((size_t)TRACE_SLOTS * f->trace_phases + 8 * f->n_wgs) * 8));
+    LA_HIP(hipMemset(f->trace, 0, ((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs) * 8));
   }
   return LA_OK;
 }
@@ -304,6 +304,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
   a.n_groups = (unsigned)ceil_div(f->n_wgs, SYNC_GROUP);
   a.trace = f->trace;
   a.trace_phases = f->trace_phases;
+  a.trace_sel = env_int("LA_TRACE_SEL", 6);
   int rc;
   {
     ProfScope ps(name, s);
@@ -317,7 +318,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
   if (rc) return rc;
   if (f->trace) {  // debugging aid: timeline of workgroup 0 (100 MHz clock) and producer statistics
     int np = n_barriers + 1;
-    std::vector<unsigned long long> h((size_t)TRACE_SLOTS * f->trace_phases + 8 * f->n_wgs);
+    std::vector<unsigned long long> h((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs);
     LA_HIP(hipStreamSynchronize(s));
     LA_HIP(hipMemcpy(h.data(), f->trace, h.size() * 8, hipMemcpyDeviceToHost));
     const int S = TRACE_SLOTS;
@@ -330,15 +331,44 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       fprintf(stderr, "[la trace]   phase %2d: +%5.2f | k-loop end %6.2f (waited for weights %6.2f) tile %6.2f epilogue %6.2f | attn: loads %6.2f loop %6.2f merged %6.2f | "
               "work end %6.2f | barrier: stores %6.2f waves %6.2f released %6.2f\n", q, since_prev, rel(1), h[S * q + 1] > t0 ? h[S * q + 3] * 0.01 : -1.0,
               rel(4), rel(5), rel(9), rel(10), rel(11), rel(2), rel(6), rel(7), rel(8));
+      if (h[S * q + 14]) {
+        fprintf(stderr, "[la trace]             attention per wave (loads issued / first block landed / blocks done):");
+        for (int w = 0; w < NCW; ++w) fprintf(stderr, " %.2f/%.2f/%.2f", rel(16 + w), rel(24 + w), rel(32 + w));
+        fprintf(stderr, "\n");
+      }
+      if (h[S * q + 14])
+        fprintf(stderr, "[la trace]             attention loop of wave 0: %d key blocks in %.2f us, of which %.2f us waiting for them\n",
+                (int)h[S * q + 14], h[S * q + 15] * 0.01, h[S * q + 13] * 0.01);
     }
     if (np > 1 && h[S * (np - 1)] > h[0])
       fprintf(stderr, "[la trace]   shader clock over the launch: %.0f MHz\n",
               (double)(h[S * (np - 1) + 12] - h[12]) / ((h[S * (np - 1)] - h[0]) * 0.01));
     double st[6] = {0, 0, 0, 0, 0, 0};
     for (int g = 0; g < f->n_wgs; ++g)
-      for (int k = 0; k < 6; ++k) st[k] += (double)h[(size_t)TRACE_SLOTS * f->trace_phases + 8 * g + k] / f->n_wgs;
+      for (int k = 0; k < 6; ++k) st[k] += (double)h[(size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * g + k] / f->n_wgs;
     fprintf(stderr, "[la trace]   producer (mean per workgroup): ring full %.1f times, %.1f polls; of %.1f us: draining before a poll %.1f us, "
             "polling for space %.1f us, waiting for the oldest chunk %.1f us\n", st[1], st[0], st[5] * 0.01, st[2] * 0.01, st[3] * 0.01, st[4] * 0.01);
+    // when each workgroup reached the barrier that ends a phase, relative to the first one there
+    for (int k = 0; k < 8 && a.trace_sel + k < np - 1; ++k) {
+      const size_t base = (size_t)TRACE_SLOTS * f->trace_phases + 8 + k;
+      unsigned long long lo = ~0ull, hi = 0;
+      for (int g = 0; g < f->n_wgs; ++g) {
+        lo = std::min(lo, h[base + (size_t)TRACE_WG * g]);
+        hi = std::max(hi, h[base + (size_t)TRACE_WG * g]);
+      }
+      double mean = 0, xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, half[2] = {0, 0};
+      int nx[8] = {0, 0, 0, 0, 0, 0, 0, 0}, nh[2] = {0, 0};
+      for (int g = 0; g < f->n_wgs; ++g) {
+        double t = (h[base + (size_t)TRACE_WG * g] - lo) * 0.01;
+        mean += t / f->n_wgs;
+        xcd[g % 8] += t; ++nx[g % 8];
+        half[g * 2 / f->n_wgs] += t; ++nh[g * 2 / f->n_wgs];
+      }
+      fprintf(stderr, "[la trace]   arrivals at the barrier after phase %d: mean %.2f last %.2f us after the first (workgroup 0: %.2f); "
+              "by workgroup %% 8:", a.trace_sel + k, mean, (hi - lo) * 0.01, (h[base] - lo) * 0.01);
+      for (int x = 0; x < 8; ++x) fprintf(stderr, " %.2f", nx[x] ? xcd[x] / nx[x] : 0.0);
+      fprintf(stderr, "; first / second half of the grid: %.2f / %.2f\n", nh[0] ? half[0] / nh[0] : 0.0, nh[1] ? half[1] / nh[1] : 0.0);
+    }
   }
   return LA_OK;
 }

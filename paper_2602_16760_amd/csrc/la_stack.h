@@ -38,6 +38,8 @@
 // All reductions have a fixed order: results are run-to-run identical, and a row's result
 // does not depend on how many rows the block has (except for the key split of attention).
 #pragma once
+#include <type_traits>
+
 #include "la_device.h"
 #include "la_internal.h"
 
@@ -63,7 +65,8 @@ constexpr int MAX_MT = LA_MAX_ROWS / 16;
 constexpr unsigned OOB = 0x80000000u;      // voffset beyond every buffer (all are < 2 GiB)
 constexpr unsigned RSRC_BYTES = 0x7fffffffu;
 constexpr int DEV = 16;                    // cache policy sc1: device-scope coherent load / store
-constexpr int TRACE_SLOTS = 16;            // timestamps per phase of the optional timeline
+constexpr int TRACE_SLOTS = 40;            // timestamps per phase of the optional timeline
+constexpr int TRACE_WG = 16;               // words per workgroup after the phases: 8 of the producer, 8 barrier arrival times
 constexpr int NT_HINT = 2;                 // cache policy nt: streamed once
 constexpr int SYNC_GROUP = 16;             // workgroups per arrival counter of the grid barrier
 constexpr int SYNC_STRIDE = 64;            // 32-bit words between barrier variables (256 B)
@@ -78,7 +81,8 @@ constexpr int LDS_RS = LDS_ML + 4 * 512;              // [64] row factors of the
 constexpr int LDS_CTL = LDS_RS + 256;                 // control words
 constexpr int LDS_CONST = LDS_CTL + 256;                // per-launch constants (LaunchConst)
 constexpr int LDS_ARGS = LDS_CONST + 128;               // per consumer wave: arguments of the GEMM pass it calls (PassArgs)
-constexpr int LDS_BYTES = LDS_ARGS + NCW * 128;
+constexpr int LDS_SINK = LDS_ARGS + NCW * 128;             // 256 B that cache-warming loads land in; never read
+constexpr int LDS_BYTES = LDS_SINK + 256;
 // control words
 constexpr int C_LANDED = 0;   // fragments of this workgroup's stream that have landed in the ring
 constexpr int C_DEAD = 1;     // a wait timed out: every wave leaves the kernel
@@ -118,7 +122,7 @@ struct LayerGains {
 struct StackArgs {
   const LayerGains *gains;
   int mode;  // 0: layer stack, 1: unembedding
-  int dbg;   // timing experiments (results are wrong when set): 1 producer moves nothing, 2 one operand k-tile, 4 no operand loads, 8 no epilogue
+  int dbg;   // timing experiments (results are wrong when set): 1 producer moves nothing, 2 one operand k-tile, 4 no operand loads, 8 no epilogue, 16 no K/V cache warming, 32 attention on the first workgroups, 64 every workgroup calls the attention
   int lb, le;
   int Bp, MT, d, Hq, Hkv, dh, F, ncg;
   float eps, inv_d;
@@ -147,8 +151,9 @@ struct StackArgs {
   float *top2;
   unsigned *sync;
   unsigned epoch0, n_groups;
-  unsigned long long *trace;  // optional: per phase 4 timestamps of workgroup 0, then per workgroup producer statistics
+  unsigned long long *trace;  // optional: per phase TRACE_SLOTS timestamps of workgroup 0, then TRACE_WG words per workgroup
   int trace_phases;
+  int trace_sel;              // every workgroup records when it reaches the barriers that end phases trace_sel .. trace_sel + 7
 };
 
 // Values that are the same in every lane, moved to scalar registers.  The compiler cannot see
@@ -273,10 +278,17 @@ __device__ __forceinline__ bool cons_barrier(Wave &wv) {
 __device__ __forceinline__ void tr_mark(unsigned long long *tr, const Wave &wv, int k) {
   if (tr && wv.w == 0 && wv.lane == 0) tr[k] = wall_clock64();
 }
+__device__ __forceinline__ void tr_mark_wave(unsigned long long *tr, const Wave &wv, int k) {  // slot k + wave
+  if (tr && wv.lane == 0) tr[k + wv.w] = wall_clock64();
+}
 
 // ---- device-scope accessors ------------------------------------------------------------------
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const void *p) {
   return __builtin_amdgcn_make_buffer_rsrc(uni_ptr(const_cast<void *>(p)), 0, RSRC_BYTES, 0x00020000);
+}
+template <int POLICY>
+__device__ __forceinline__ u32x4 ld128p(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, POLICY));
 }
 __device__ __forceinline__ u32x4 ld128(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, DEV);
@@ -952,8 +964,47 @@ struct AttArgs {
   uint16_t *attn_out;
   const uint64_t *vis;
   unsigned lds0;
+  int u0;  // this workgroup's first unit (the next ones follow at gridDim.x)
   unsigned long long *tr;
 };
+
+// Which workgroups run the attention units.  When the QKV tiles do not divide evenly, the
+// workgroups behind the first (ntiles mod G) have one tile fewer and reach the end of the QKV
+// phase early: if there are enough of them they take the units (and warm the cache for them
+// meanwhile, see kv_touch).  Returns the workgroup of unit 0.
+__device__ __forceinline__ int att_first_wg(int qkv_tiles, int n_units) {
+  const int G = gridDim.x, heavy = qkv_tiles % G;
+  return G - heavy >= n_units ? heavy : 0;
+}
+
+// Requests the cache lines of the committed K, V rows of one kv head that this unit's share
+// covers: key blocks that end at or before row L, which the attention then reads with ordinary
+// loads and finds in the XCD's L2 (all units of a kv head sit on one XCD).  Issued when the
+// workgroup has finished its QKV tiles; the lines travel while it waits at the barrier.  One
+// 4-byte load per 128-byte line into a sink in LDS: nothing is kept.
+__device__ __forceinline__ void kv_touch(const uint16_t *Kc, const uint16_t *Vc, int u, int n_rt, int Hkv, int dh, int L, const Wave &wv,
+                                         unsigned lds0) {
+  const int rt = u / Hkv, kvh = u - rt * Hkv;
+  const int kb_split = L >> 5;
+  const int k_lines_row = dh >> 6, v_lines_blk = dh >> 1;  // 128-byte lines per K row of a head / per V key block of a head
+  if (k_lines_row == 0) return;                            // (head_dim 64 and 128 only reach here)
+  const int nlk = kb_split * 32 * k_lines_row, nl = nlk + kb_split * v_lines_blk;
+  __amdgpu_buffer_rsrc_t rk = rsrc_of(Kc), rv = rsrc_of(Vc);
+  LDS_AS void *sink = (LDS_AS void *)(uintptr_t)(lds0 + LDS_SINK);
+  for (int t0 = (rt * NCW + wv.w) * 64; t0 < nl; t0 += n_rt * NCW * 64) {
+    const int t = t0 + wv.lane;
+    unsigned ko = OOB, vo = OOB;
+    if (t < nlk) {
+      const int row = t / k_lines_row, part = t - row * k_lines_row;
+      ko = (unsigned)((((size_t)row * Hkv + kvh) * dh) * 2 + part * 128);
+    } else if (t < nl) {
+      const int j = t - nlk, kb = j / v_lines_blk, l = j - kb * v_lines_blk;
+      vo = (unsigned)((((size_t)kb * Hkv + kvh) * dh * 32) * 2 + l * 128);
+    }
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, sink, 4, ko, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, sink, 4, vo, 0, 0, 0);
+  }
+}
 
 template <int DH>
 __device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveState st_in) {
@@ -982,7 +1033,9 @@ __device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveSt
   const int w = wv.w, lane = wv.lane, q4 = lane >> 4, c16 = lane & 15;
   const int g = a.Hq / a.Hkv, n_rt = g * a.MT;
   const int total = L + a.Bp, nkb = (total + 31) >> 5;
-  for (int u = blockIdx.x; u < a.Hkv * n_rt; u += gridDim.x) {
+  for (int u = uni(p.u0); u < a.Hkv * n_rt; u += gridDim.x) {
+    // kv head = unit mod Hkv: consecutive workgroups sit on different XCDs, so with eight kv heads
+    // all units of a head share one XCD's L2 and its K, V are fetched from memory once
     const int kvh = u / n_rt, rt = u - kvh * n_rt;
     const int b = (rt % a.MT) * 16 + c16;  // block row of this lane's q-row
     const uint64_t vb = b < a.Bp ? a.vis[b] : 0ull;
@@ -994,53 +1047,65 @@ __device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveSt
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -1e30f, l_run = 0.f;
-    u32x4 ka[KT], kbv[KT], vt[DT], nka[KT], nkbv[KT], nvt[DT];
-    auto load_kv = [&](int kb, u32x4 *pa, u32x4 *pb, u32x4 *pv) {
-      const unsigned k_off = kb < nkb ? (unsigned)((((size_t)(kb * 32 + c16) * a.Hkv + kvh) * DH + 8 * q4) * 2) : OOB;
-      const unsigned v_off = kb < nkb ? (unsigned)(((((size_t)kb * a.Hkv + kvh) * DH + c16) * 32 + 8 * q4) * 2) : OOB;
+    // Key blocks that end at or before row L ("early") were written by earlier launches:
+    // ordinary cached loads (they hit in L2 when warmed, see kv_touch), and every key is visible.
+    // A block that holds rows of this step ("late") was written by other workgroups in the phase
+    // before: device-scope loads, and the mask applies.  A wave takes its late block first (there
+    // are at most three, dealt to the waves from the last one down), then its early blocks
+    // w, w + 7, ...  One register set for K and one for V: the next block's K is requested as soon
+    // as the scores are out of the matrix unit and travels during the softmax and P V; the next V
+    // follows P V and travels during the next scores.  Every load in the loop is of the same kind
+    // and unconditional (a block beyond the last is requested out of range: nothing moves), so
+    // the count of outstanding loads stays exact; and the function stays within the registers
+    // that a callee may use without saving them.
+    u32x4 ka[KT], kb2[KT], vt[DT];
+    auto load_k = [&](auto policy, int kb, bool valid) {
+      constexpr int POL = decltype(policy)::value;
+      const unsigned k_off = valid ? (unsigned)((((size_t)(kb * 32 + c16) * a.Hkv + kvh) * DH + 8 * q4) * 2) : OOB;
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
-        pa[kt] = ld128(rk, k_off + kt * 64);
-        pb[kt] = ld128(rk, k_off + (unsigned)(16 * a.Hkv * DH * 2) + kt * 64);
+        ka[kt] = ld128p<POL>(rk, k_off + kt * 64);
+        kb2[kt] = ld128p<POL>(rk, k_off + (unsigned)(16 * a.Hkv * DH * 2) + kt * 64);
       }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) pv[dt] = ld128(rv, v_off + dt * 16 * 32 * 2);
     };
-    load_kv(w, nka, nkbv, nvt);
-    if (u == blockIdx.x) {
-      wait_vmcnt<0>();
-      tr_mark(tr, wv, 9);
-    }
-    for (int kb = w; kb < nkb; kb += NCW) {
+    auto load_v = [&](auto policy, int kb, bool valid) {
+      constexpr int POL = decltype(policy)::value;
+      const unsigned v_off = valid ? (unsigned)(((((size_t)kb * a.Hkv + kvh) * DH + c16) * 32 + 8 * q4) * 2) : OOB;
 #pragma unroll
-      for (int kt = 0; kt < KT; ++kt) {
-        ka[kt] = nka[kt];
-        kbv[kt] = nkbv[kt];
-      }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) vt[dt] = nvt[dt];
-      load_kv(kb + NCW, nka, nkbv, nvt);  // the next block's tiles travel while this one is used
+      for (int dt = 0; dt < DT; ++dt) vt[dt] = ld128p<POL>(rv, v_off + dt * 16 * 32 * 2);
+    };
+    // scores of the block in ka / kb2: lane holds keys kb*32 + 4 q4 + i (sv[0..3]) and
+    // kb*32 + 16 + 4 q4 + i (sv[4..7]) of q-row c16
+    auto scores = [&](float *sv) {
       f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
         sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt]), q[kt], sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbv[kt]), q[kt], sb, 0, 0, 0);
+        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb2[kt]), q[kt], sb, 0, 0, 0);
       }
-      // lane holds keys kb*32 + 4 q4 + i (sa) and kb*32 + 16 + 4 q4 + i (sb) of q-row c16
-      float sv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sv[i] = i < 4 ? sa[i] : sb[i - 4];
+    };
+    // running softmax over the block's scores; returns the probabilities as a matrix operand
+    auto softmax = [&](auto masked, const float *sv, int kb, float &corr) {
+      constexpr bool MASKED = decltype(masked)::value;
       bool ok[8];
       float mx = -1e30f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        int key = kb * 32 + (i >> 2) * 16 + 4 * q4 + (i & 3);
-        sv[i] = i < 4 ? sa[i] : sb[i - 4];
-        ok[i] = key < L || (key < total && ((vb >> (key - L)) & 1ull));
-        if (ok[i]) mx = fmaxf(mx, sv[i]);
+        if (MASKED) {
+          const int key = kb * 32 + (i >> 2) * 16 + 4 * q4 + (i & 3);
+          ok[i] = key < L || (key < total && ((vb >> (key - L)) & 1ull));
+          if (ok[i]) mx = fmaxf(mx, sv[i]);
+        } else {
+          ok[i] = true;
+          mx = fmaxf(mx, sv[i]);
+        }
       }
       mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      float m_new = fmaxf(m_run, mx);
-      float corr = __expf(m_run - m_new);
+      const float m_new = fmaxf(m_run, mx);
+      corr = __expf(m_run - m_new);
       float p[8], ps = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -1051,15 +1116,66 @@ __device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveSt
       ps += __shfl_xor(ps, 32, 64);
       l_run = l_run * corr + ps;
       m_run = m_new;
-      u32x4 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-      bf16x8 pb = __builtin_bit_cast(bf16x8, pw);
+      const u32x4 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+      return __builtin_bit_cast(bf16x8, pw);
+    };
+    auto pv = [&](bf16x8 pb, float corr) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         o[dt] *= corr;
         o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[dt]), pb, o[dt], 0, 0, 0);
       }
+    };
+    static_assert(LA_MAX_ROWS <= 64, "at most three late key blocks: one per wave");
+    const std::integral_constant<int, 0> plain{};
+    const std::integral_constant<int, DEV> coherent{};
+    const int kb_split = L >> 5;                // early blocks: 0 .. kb_split - 1
+    const int late = kb_split + (NCW - 1 - w);  // this wave's late block, if it exists
+    const bool has_late = late < nkb;
+    const bool any = has_late || w < kb_split;
+    int kb = has_late ? late : w;               // the block in the registers
+    int ne = has_late ? w : w + NCW;            // the next early block to request
+    if (has_late) {
+      load_k(coherent, late, true);
+      load_v(coherent, late, true);
+    } else {
+      load_k(plain, w, w < kb_split);
+      load_v(plain, w, w < kb_split);
     }
-    if (u == blockIdx.x) tr_mark(tr, wv, 10);
+    tr_mark_wave(tr, wv, 16);  // loads issued
+    if (tr) {
+      wait_vmcnt<DT>();
+      tr_mark(tr, wv, 9);
+      tr_mark_wave(tr, wv, 24);  // first K tiles (and q) landed
+    }
+    unsigned long long n_iter = 0;
+    const unsigned long long t_loop = tr ? wall_clock64() : 0ull;
+    if (any) {
+      float sv[8], corr;
+      scores(sv);
+      load_k(plain, ne, ne < kb_split);
+      const bf16x8 pb = has_late ? softmax(std::true_type{}, sv, kb, corr) : softmax(std::false_type{}, sv, kb, corr);
+      pv(pb, corr);
+      load_v(plain, ne, ne < kb_split);
+      ++n_iter;
+      while (ne < kb_split) {
+        kb = ne;
+        ne += NCW;
+        scores(sv);
+        load_k(plain, ne, ne < kb_split);
+        const bf16x8 pb2 = softmax(std::false_type{}, sv, kb, corr);
+        pv(pb2, corr);
+        load_v(plain, ne, ne < kb_split);
+        ++n_iter;
+      }
+    }
+    tr_mark(tr, wv, 10);
+    tr_mark_wave(tr, wv, 32);  // key blocks done
+    if (tr && w == 0 && lane == 0) {
+      tr[13] = 0;
+      tr[14] = n_iter;
+      tr[15] = wall_clock64() - t_loop;
+    }
     // merge the seven partial results: ((w0 + w4) + (w2 + w6)) + (w3 + (w1 + w5))
     auto put = [&](int buf) {
 #pragma unroll
@@ -1089,7 +1205,7 @@ __device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveSt
     if (w == 0) {
       if (!ctl_wait_ge(wv, C_TREE + 3, qs + 3)) return wv.st;
       merge(1);
-      if (u == blockIdx.x) tr_mark(tr, wv, 11);
+      tr_mark(tr, wv, 11);
       // o[dt][i] = O^T[channel 16 dt + 4 q4 + i][q-row c16]: four channels = half a 16-byte piece
       if (b < a.Bp) {
         const float inv = 1.0f / l_run;
@@ -1172,7 +1288,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   const unsigned f_un = ((unsigned)(my_tiles(a.un.ntiles) * a.un.KT) + CHUNK - 1) / CHUNK * CHUNK;
 
   if (wave == NCW) {
-    unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + 8 * blockIdx.x : nullptr;
+    unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x : nullptr;
     if (a.mode == 0) producer(a, ctl, lds + LDS_RING, (unsigned)a.lb, (unsigned)(a.le - a.lb), f_layer, a.seg_frags, st);
     else producer(a, ctl, lds + LDS_RING, 0u, 1u, f_un, a.seg_frags, st);
     return;
@@ -1193,10 +1309,18 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   // GEMM, FINAL.  The GEMM passes and the attention are functions of their own; this loop only
   // sets up their arguments and runs the grid barrier between phases.
   const int n_phases = a.mode == 1 ? 3 : 1 + 5 * (a.le - a.lb);
+  const int n_rt = a.Hq / a.Hkv * MT, n_units = a.Hkv * n_rt;
+  const int att_first = (a.dbg & 32) ? 0 : att_first_wg(a.qkv.ntiles, n_units);
+  const int att_u0 = (int)blockIdx.x >= att_first ? (int)blockIdx.x - att_first : n_units;  // no unit: n_units
   unsigned sbase = 0;
   unsigned long long *tr = nullptr;  // timeline slots of the current phase (workgroup 0 only)
   for (int ph = 0; ph < n_phases; ++ph) {
-    if (ph > 0 && !grid_sync(a, wv, ++epoch, tr)) return;
+    if (ph > 0) {
+      const int k = ph - 1 - a.trace_sel;
+      if (a.trace && k >= 0 && k < 8 && wv.w == 0 && wv.lane == 0)
+        a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + 8 + k] = wall_clock64();
+      if (!grid_sync(a, wv, ++epoch, tr)) return;
+    }
     tr = (a.trace && blockIdx.x == 0 && ph < a.trace_phases) ? a.trace + TRACE_SLOTS * ph : nullptr;
     tr_mark(tr, wv, 0);
     if (tr && wv.w == 0 && wv.lane == 0) tr[12] = clock64();  // shader clock, to report the running frequency
@@ -1226,14 +1350,17 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
         p.A = xa0; p.mode = MODE_QKV; p.rsq_in = rsq0; p.q.Kc = Kc; p.q.Vc = Vc;
         g = a.qkv; have_g = true; frags = f_qkv;
         break;
-      case 2: {
-        AttArgs t;
-        t.Kc = Kc; t.Vc = Vc; t.attn_out = attn_l; t.vis = a.vis; t.lds0 = lds0; t.tr = tr;
-        wv.st = a.dh == 128 ? attention_phase<128>(t, wv.st) : attention_phase<64>(t, wv.st);
-        wv.st.ok = uni(wv.st.ok);
-        if (!wv.st.ok) return;
+      case 2:
+        if (att_u0 < n_units || (a.dbg & 64)) {  // (a call costs the callee's register saves: only where there is work)
+          AttArgs t;
+          t.Kc = Kc; t.Vc = Vc; t.attn_out = attn_l; t.vis = a.vis; t.lds0 = lds0; t.u0 = att_u0;
+          // (the timeline shows the attention of the workgroup that runs unit 0)
+          t.tr = (a.trace && att_u0 == 0 && ph < a.trace_phases) ? a.trace + TRACE_SLOTS * ph : nullptr;
+          wv.st = a.dh == 128 ? attention_phase<128>(t, wv.st) : attention_phase<64>(t, wv.st);
+          wv.st.ok = uni(wv.st.ok);
+          if (!wv.st.ok) return;
+        }
         break;
-      }
       case 3:
         p.A = attn_l; p.mode = MODE_RESID; p.q.gain = a.gains[layer].g_mlp; p.q.xa_out = xa1; p.q.rsq_out = rsq1;
         g = a.o; have_g = true; frags = f_o;
@@ -1274,6 +1401,8 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
       wv.st = gemm_phase<MT>(p, wv.st, g, lds0, wv.w);
       if (!wv.st.ok) return;
       sbase += frags;
+      if (sub == 1 && !(a.dbg & 16))
+        for (int u = att_u0; u < n_units; u += gridDim.x) kv_touch(Kc, Vc, u, n_rt, a.Hkv, a.dh, L, wv, lds0);
     }
     tr_mark(tr, wv, 2);
   }
