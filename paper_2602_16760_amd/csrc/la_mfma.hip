@@ -78,9 +78,15 @@ __global__ void pack_weights_kernel(PackSrc p, PackDst d) {
     int k0 = kt * 32 + 8 * (lane >> 4);
     int ld;
     const uint16_t *src = pack_col(p, pc, ld);
+    // bf16 -> half precision: exact for every weight of magnitude 2^-14 or more (8 significant
+    // bits fit in 11); smaller ones land on the subnormal grid, at most 2^-25 away
     uint16_t v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = src[(size_t)(k0 + i) * ld];
+    for (int i = 0; i < 8; ++i) {
+      const float w = __uint_as_float((uint32_t)src[(size_t)(k0 + i) * ld] << 16);
+      const float lim = 65504.0f;
+      v[i] = __builtin_bit_cast(uint16_t, (_Float16)fminf(fmaxf(w, -lim), lim));
+    }
     uint4 o;
     o.x = v[0] | ((uint32_t)v[1] << 16);
     o.y = v[2] | ((uint32_t)v[3] << 16);
@@ -187,7 +193,7 @@ int mfma_create(la_model *m) {
   f->seg_frags = (unsigned)(f->p_qkv.nt_max * f->p_qkv.KT + f->p_o.nt_max * f->p_o.KT + f->p_gu.nt_max * f->p_gu.KT +
                             f->p_down.nt_max * f->p_down.KT);
   f->seg_frags = (f->seg_frags + CHUNK - 1) / CHUNK * CHUNK;  // the producer moves whole chunks
-  f->cu_bytes = (size_t)d.n_layers * f->seg_frags * 1024 + (size_t)env_int("LA_CU_PAD", 0) / 256 * 256;
+  f->cu_bytes = (size_t)d.n_layers * f->seg_frags * 1024;
   LA_REQUIRE(f->cu_bytes < ((size_t)1 << 31), LA_EINVAL, "one CU's weight stream exceeds 2 GiB");
   f->ucu_bytes = (size_t)(((size_t)f->p_un.nt_max * f->p_un.KT + CHUNK - 1) / CHUNK * CHUNK) * 1024;
   LA_REQUIRE(f->ucu_bytes < ((size_t)1 << 31), LA_EINVAL, "one CU's unembedding stream exceeds 2 GiB");

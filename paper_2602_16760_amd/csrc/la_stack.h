@@ -46,6 +46,7 @@
 namespace la {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef _Float16 __attribute__((ext_vector_type(8))) f16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned u32x2;
@@ -82,7 +83,12 @@ constexpr int LDS_CTL = LDS_RS + 256;                 // control words
 constexpr int LDS_CONST = LDS_CTL + 256;                // per-launch constants (LaunchConst)
 constexpr int LDS_ARGS = LDS_CONST + 128;               // per consumer wave: arguments of the GEMM pass it calls (PassArgs)
 constexpr int LDS_SINK = LDS_ARGS + NCW * 128;             // 256 B that cache-warming loads land in; never read
-constexpr int LDS_BYTES = LDS_SINK + 256;
+constexpr int X_TILES = 2;                                 // 1 KB tiles of the residual stream a workgroup can keep in LDS
+constexpr int LDS_X = LDS_SINK + 256;                      // this workgroup's columns of x: [column tile][row][16] floats
+constexpr int LDS_GAIN = LDS_X + X_TILES * 1024;           // the norm gains of those columns for the running phase: [column tile][16]
+constexpr int LDS_BYTES = LDS_GAIN + 256;                  // (a whole wave's 4-byte loads land there: 256 B)
+static_assert(X_TILES * 16 <= 64, "one load instruction stages the gains");
+static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
 // control words
 constexpr int C_LANDED = 0;   // fragments of this workgroup's stream that have landed in the ring
 constexpr int C_DEAD = 1;     // a wait timed out: every wave leaves the kernel
@@ -122,7 +128,7 @@ struct LayerGains {
 struct StackArgs {
   const LayerGains *gains;
   int mode;  // 0: layer stack, 1: unembedding
-  int dbg;   // timing experiments (results are wrong when set): 1 producer moves nothing, 2 one operand k-tile, 4 no operand loads, 8 no epilogue, 16 no K/V cache warming, 32 attention on the first workgroups, 64 every workgroup calls the attention
+  int dbg;   // timing experiments (results are wrong when set): 1 producer moves nothing, 2 one operand k-tile, 4 no operand loads, 8 no epilogue, 16 no K/V cache warming, 32 attention on the first workgroups, 64 every workgroup calls the attention, 128 x stays in memory
   int lb, le;
   int Bp, MT, d, Hq, Hkv, dh, F, ncg;
   float eps, inv_d;
@@ -172,6 +178,7 @@ __device__ __forceinline__ T *uni_ptr(T *p) {
 // arguments (a function's arguments beyond 32 registers go through memory).
 struct LaunchConst {
   int Bp, MT, d, ncg, Hq, Hkv, dh, L, dbg;
+  int x_lds;  // this workgroup keeps its columns of the residual stream in LDS (LDS_X)
   float inv_d, eps;
   float *x;
   const float *cs;
@@ -182,7 +189,7 @@ __device__ __forceinline__ LaunchConst launch_const(unsigned lds0) {
   LDS_AS const LaunchConst *p = (LDS_AS const LaunchConst *)(uintptr_t)(lds0 + LDS_CONST);
   LaunchConst c;
   c.Bp = uni(p->Bp); c.MT = uni(p->MT); c.d = uni(p->d); c.ncg = uni(p->ncg); c.Hq = uni(p->Hq); c.Hkv = uni(p->Hkv);
-  c.dh = uni(p->dh); c.L = uni(p->L); c.dbg = uni(p->dbg);
+  c.dh = uni(p->dh); c.L = uni(p->L); c.dbg = uni(p->dbg); c.x_lds = uni(p->x_lds);
   c.inv_d = __uint_as_float(uni(__float_as_uint(p->inv_d)));
   c.eps = __uint_as_float(uni(__float_as_uint(p->eps)));
   c.x = uni_ptr(p->x); c.cs = uni_ptr(p->cs); c.qf = uni_ptr(p->qf);
@@ -310,6 +317,15 @@ __device__ __forceinline__ void st16(__amdgpu_buffer_rsrc_t r, unsigned byte_off
 }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return (uint32_t)float_to_bf16(lo) | ((uint32_t)float_to_bf16(hi) << 16);
+}
+// Two activations as IEEE half precision (round to nearest even; beyond the format's range: the
+// largest finite value).  The weight GEMMs take their operands in this format: the bf16 weights
+// convert to it without loss (see pack_weights_kernel), and an activation keeps 11 significant
+// bits instead of 8, which removes most of the rounding noise of a deep stack.
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+  const float lim = 65504.0f;
+  const _Float16 a = (_Float16)fminf(fmaxf(lo, -lim), lim), b = (_Float16)fminf(fmaxf(hi, -lim), lim);
+  return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
 }
 // byte offset of the 16-byte piece (row b, columns col..col+7, col a multiple of 8) of an
 // operand-fragment buffer with MT row tiles
@@ -639,11 +655,24 @@ __device__ __attribute__((noinline)) void gemm_epilogue(EpiInts e) {
       const int col = 16 * gt + 8 * oct;
       f32x4 *xp = reinterpret_cast<f32x4 *>(lc.x + (size_t)b * d + col);
       LDS_AS const float *tr = tile + b * LDT + 16 * tt + 8 * oct;
-      f32x4 x0 = xp[0], x1 = xp[1];
+      // (x in LDS: no load from memory stands between the reduction and the stores)
+      LDS_AS f32x4 *xs = (LDS_AS f32x4 *)(uintptr_t)(lds0 + LDS_X + (((tile_first + tt) * 16 * MT + b) * 16 + 8 * oct) * 4);
+      f32x4 x0, x1;
+      if (lc.x_lds) {
+        x0 = xs[0];
+        x1 = xs[1];
+      } else {
+        x0 = xp[0];
+        x1 = xp[1];
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         x0[i] += tr[i];
         x1[i] += tr[4 + i];
+      }
+      if (lc.x_lds) {
+        xs[0] = x0;
+        xs[1] = x1;
       }
       xp[0] = x0;
       xp[1] = x1;
@@ -653,9 +682,21 @@ __device__ __attribute__((noinline)) void gemm_epilogue(EpiInts e) {
       sq += __shfl_xor(sq, 1, 64);
       if (q.gain) {
         if (oct == 0) st32f(rsrc_of(q.rsq_out), (unsigned)(b * ncg + gt) * 4, sq);
-        const float *gp = q.gain + col;
-        u32x4 v = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
-                   pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+        float gp[8];
+        if (lc.x_lds) {  // staged at the start of the phase (gain_stage)
+          LDS_AS const f32x4 *gs = (LDS_AS const f32x4 *)(uintptr_t)(lds0 + LDS_GAIN + ((tile_first + tt) * 16 + 8 * oct) * 4);
+          const f32x4 g0 = gs[0], g1 = gs[1];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            gp[i] = g0[i];
+            gp[4 + i] = g1[i];
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) gp[i] = q.gain[col + i];
+        }
+        u32x4 v = {pack_f16(x0[0] * gp[0], x0[1] * gp[1]), pack_f16(x0[2] * gp[2], x0[3] * gp[3]),
+                   pack_f16(x1[0] * gp[4], x1[1] * gp[5]), pack_f16(x1[2] * gp[6], x1[3] * gp[7])};
         st128(rsrc_of(q.xa_out), frag_piece(col, b, MT), v);
       }
     }
@@ -674,7 +715,7 @@ __device__ __attribute__((noinline)) void gemm_epilogue(EpiInts e) {
         act[i] = g / (1.0f + __expf(-g)) * u;
       }
       st128(rp, frag_piece(8 * gt, b, MT),
-            u32x4{pack_bf16(act[0], act[1]), pack_bf16(act[2], act[3]), pack_bf16(act[4], act[5]), pack_bf16(act[6], act[7])});
+            u32x4{pack_f16(act[0], act[1]), pack_f16(act[2], act[3]), pack_f16(act[4], act[5]), pack_f16(act[6], act[7])});
     }
   } else {  // MODE_UNEMBED: arg-max of each row over this chunk's columns, 4 threads per row
     const int row = tid >> 2, j = tid & 3;
@@ -794,8 +835,8 @@ __device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveS
       for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int t = 0; t < NT; ++t)
-          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rA[s][mt]),
-                                                                __builtin_bit_cast(bf16x8, rW[t]), acc[mt][t], 0, 0, 0);
+          acc[mt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, rA[s][mt]),
+                                                               __builtin_bit_cast(f16x8, rW[t]), acc[mt][t], 0, 0, 0);
       // this k-tile's reads are in the LDS queue before the write below: when the producer sees
       // the new value, the slots have been read (LDS traffic does not disturb the load counting)
       // Written by every lane, and to a spare word for a slot beyond the last k-tile: a branch
@@ -917,6 +958,27 @@ __device__ __forceinline__ WaveState gemm_phase(PassArgs p, WaveState st, const 
 // ---- first operand of a launch: norm statistics and fragments of x * gain ----------------------
 // One thread per (row, 8 columns).  Sums of squares are kept per 16 columns, the granularity of
 // the GEMM epilogues that produce them in later phases.
+// This workgroup's columns of x (column tiles blockIdx.x, blockIdx.x + G, ...) into LDS_X.
+__device__ __forceinline__ void x_stage(const StackArgs &a, const Wave &wv, unsigned lds0, int nt_x) {
+  const int rows = 16 * a.MT;
+  for (int it = wv.w * 64 + wv.lane; it < nt_x * a.Bp * 4; it += CONS_THREADS) {
+    const int part = it & 3, bt = it >> 2, tt = bt / a.Bp, b = bt - tt * a.Bp;
+    const int col = 16 * ((int)blockIdx.x + (int)gridDim.x * tt) + 4 * part;
+    *(LDS_AS f32x4 *)(uintptr_t)(lds0 + LDS_X + ((tt * rows + b) * 16 + 4 * part) * 4) =
+        *reinterpret_cast<const f32x4 *>(a.x + (size_t)b * a.d + col);
+  }
+}
+
+// The gains of this workgroup's x columns into LDS_GAIN, straight from memory into LDS: issued by
+// wave 0 before its GEMM pass, landed long before the epilogue reads them (a wave's loads return
+// in order, and wave 0 has waited for its operand loads by then).
+__device__ __forceinline__ void gain_stage(const float *gain, const Wave &wv, unsigned lds0, int nt_x) {
+  if (wv.w != 0 || gain == nullptr) return;
+  const int tt = wv.lane >> 4;
+  const unsigned vo = tt < nt_x ? (unsigned)((16 * ((int)blockIdx.x + (int)gridDim.x * tt) + (wv.lane & 15)) * 4) : OOB;
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_of(gain), (LDS_AS void *)(uintptr_t)(lds0 + LDS_GAIN), 4, vo, 0, 0, 0);
+}
+
 __device__ __forceinline__ void prep_phase(const StackArgs &a, const Wave &wv, const float *gain, uint16_t *xa_out, float *rsq_out) {
   __amdgpu_buffer_rsrc_t rq = rsrc_of(rsq_out), rx = rsrc_of(xa_out);
   const int octs = a.d >> 3, total = a.Bp * octs;
@@ -930,8 +992,8 @@ __device__ __forceinline__ void prep_phase(const StackArgs &a, const Wave &wv, c
     sq += __shfl_xor(sq, 1, 64);  // octs is even: both octets of a 16-column group sit in one wave
     if ((oct & 1) == 0) st32f(rq, (unsigned)(r * a.ncg + (oct >> 1)) * 4, sq);
     const float *gp = gain + c0;
-    u32x4 v = {pack_bf16(x0[0] * gp[0], x0[1] * gp[1]), pack_bf16(x0[2] * gp[2], x0[3] * gp[3]),
-               pack_bf16(x1[0] * gp[4], x1[1] * gp[5]), pack_bf16(x1[2] * gp[6], x1[3] * gp[7])};
+    u32x4 v = {pack_f16(x0[0] * gp[0], x0[1] * gp[1]), pack_f16(x0[2] * gp[2], x0[3] * gp[3]),
+               pack_f16(x1[0] * gp[4], x1[1] * gp[5]), pack_f16(x1[2] * gp[6], x1[3] * gp[7])};
     st128(rx, frag_piece(c0, r, a.MT), v);
   }
 }
@@ -1214,7 +1276,7 @@ __device__ __attribute__((noinline)) WaveState attention_phase(AttArgs p, WaveSt
         for (int dt = 0; dt < DT; ++dt) {
           int col = (kvh * g + j) * DH + 16 * dt + 8 * (q4 >> 1);
           st64(ra, frag_piece(col, b, a.MT) + 8 * (q4 & 1),
-               u32x2{pack_bf16(o[dt][0] * inv, o[dt][1] * inv), pack_bf16(o[dt][2] * inv, o[dt][3] * inv)});
+               u32x2{pack_f16(o[dt][0] * inv, o[dt][1] * inv), pack_f16(o[dt][2] * inv, o[dt][3] * inv)});
         }
       }
       signal(qs + 4);
@@ -1275,6 +1337,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   if (threadIdx.x == 64) {
     LDS_AS LaunchConst *c = (LDS_AS LaunchConst *)(lds + LDS_CONST);
     c->Bp = a.Bp; c->MT = MT; c->d = a.d; c->ncg = a.ncg; c->Hq = a.Hq; c->Hkv = a.Hkv; c->dh = a.dh; c->L = L; c->dbg = a.dbg;
+    c->x_lds = (a.mode == 0 && my_tiles(a.o.ntiles) * MT <= X_TILES && !(a.dbg & 128)) ? 1 : 0;
     c->inv_d = a.inv_d; c->eps = a.eps; c->x = a.x; c->cs = a.cs; c->qf = a.qf;
   }
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
@@ -1309,6 +1372,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   // GEMM, FINAL.  The GEMM passes and the attention are functions of their own; this loop only
   // sets up their arguments and runs the grid barrier between phases.
   const int n_phases = a.mode == 1 ? 3 : 1 + 5 * (a.le - a.lb);
+  const bool x_lds = launch_const(lds0).x_lds != 0;
   const int n_rt = a.Hq / a.Hkv * MT, n_units = a.Hkv * n_rt;
   const int att_first = (a.dbg & 32) ? 0 : att_first_wg(a.qkv.ntiles, n_units);
   const int att_u0 = (int)blockIdx.x >= att_first ? (int)blockIdx.x - att_first : n_units;  // no unit: n_units
@@ -1344,6 +1408,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
         } else {
           prep_phase(a, wv, a.gains[layer].g_attn, xa0, rsq0);
           rope_table_phase(a, wv);
+          if (x_lds) x_stage(a, wv, lds0, my_tiles(a.o.ntiles));
         }
         break;
       case 1:
@@ -1364,6 +1429,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
       case 3:
         p.A = attn_l; p.mode = MODE_RESID; p.q.gain = a.gains[layer].g_mlp; p.q.xa_out = xa1; p.q.rsq_out = rsq1;
         g = a.o; have_g = true; frags = f_o;
+        if (x_lds) gain_stage(p.q.gain, wv, lds0, my_tiles(a.o.ntiles));
         break;
       case 4:
         p.A = xa1; p.mode = MODE_GATEUP; p.rsq_in = rsq1; p.q.act_a = act_l;
@@ -1375,6 +1441,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
         p.q.gain = layer + 1 < a.le ? a.gains[layer + 1].g_attn : nullptr;
         p.q.xa_out = xa0 + 2 * a.xa_stride; p.q.rsq_out = rsq0 + 2 * a.rsq_stride;
         g = a.down; have_g = true; frags = f_layer - f_qkv - f_o - f_gu;  // with the layer's padding
+        if (x_lds) gain_stage(p.q.gain, wv, lds0, my_tiles(a.o.ntiles));
         break;
       case 6: {
         // every CU writes all of its partial records: the ones it has no tiles for stay empty
