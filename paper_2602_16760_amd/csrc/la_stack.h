@@ -138,6 +138,9 @@ struct StackArgs {
   const uint8_t *wstream;
   size_t cu_bytes;
   unsigned seg_frags;
+  unsigned pace;  // shader-clock cycles a producer lets pass between two chunks (0: as fast as it can).
+                  // A little above the memory's share per CU: without it the producers' bursts after
+                  // every stall fill the memory queues, and the measured step is 1-2 % longer.
   float *x;
   const int32_t *pos;
   const uint64_t *vis;
@@ -431,6 +434,8 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
     free_until = m + NSLOT;
   };
   unsigned idle_spins = 0;
+  const unsigned pace = uni(a.pace);
+  unsigned long long t_issue = 0;
   while (next < total) {
     if (next + CHUNK > free_until) {
       read_space();
@@ -458,6 +463,10 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
         idle_spins = 0;
         if (tr) t_poll += wall_clock64() - t0;
       }
+    }
+    if (pace) {
+      while ((unsigned long long)clock64() - t_issue < pace) __builtin_amdgcn_s_sleep(1);
+      t_issue = (unsigned long long)clock64();
     }
     {
       // a chunk is contiguous in memory and in the ring (segments are padded to whole chunks):
