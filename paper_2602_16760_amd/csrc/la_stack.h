@@ -1304,10 +1304,19 @@ __device__ __forceinline__ void unembed_final_phase(const StackArgs &a, const Wa
   const int n_part = gridDim.x * a.un_parts_per_cu;
   for (int b = blockIdx.x * NCW + wv.w; b < a.Bp; b += gridDim.x * NCW) {
     Top best{-INFINITY, 0x7fffffff, -INFINITY};
-    for (int s = wv.lane; s < n_part; s += 64) {
-      unsigned o = (unsigned)(((size_t)s * 64 + b) * sizeof(Top));
-      Top c{ld32f(ru, o), (int)__builtin_amdgcn_raw_buffer_load_b32(ru, o + 4, 0, DEV), ld32f(ru, o + 8)};
-      best = top_merge2(best, c);
+    // eight records per lane and turn, all requested before the first is merged (a record beyond
+    // the last is requested out of range and reads as zeros: it is skipped)
+    for (int s0 = wv.lane; s0 < n_part; s0 += 64 * 8) {
+      Top c[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int s = s0 + 64 * j;
+        const unsigned o = s < n_part ? (unsigned)(((size_t)s * 64 + b) * sizeof(Top)) : OOB;
+        c[j] = Top{ld32f(ru, o), (int)__builtin_amdgcn_raw_buffer_load_b32(ru, o + 4, 0, DEV), ld32f(ru, o + 8)};
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (s0 + 64 * j < n_part) best = top_merge2(best, c[j]);
     }
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
