@@ -24,7 +24,11 @@
  *    enqueue work and do not synchronise unless stated.
  *  - Matrices are row-major [in, out].  dtype LA_F32: weights and cache are float;
  *    LA_BF16: weights and cache are bfloat16 bit patterns.  The residual stream (`hidden`),
- *    norm gains, softmax and all accumulations are float in both cases.
+ *    norm gains, softmax and all accumulations are float in both cases.  In LA_BF16 the
+ *    weight matrices are multiplied as IEEE half precision (a bfloat16 weight of magnitude
+ *    2^-14 or more converts without loss, smaller ones to within 2^-25) with activations
+ *    rounded to half precision (values beyond +-65504 saturate); attention multiplies in
+ *    bfloat16.
  *  - A block has Bp <= LA_MAX_ROWS rows.  Row b sits at cache row L+b while the block is
  *    in flight, where L is the committed cache length kept on the device inside la_kv.
  */

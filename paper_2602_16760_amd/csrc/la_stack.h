@@ -1,4 +1,4 @@
-// bf16 MFMA path for gfx950: the whole layer stack of a verification step as ONE persistent
+// MFMA path for gfx950 (bf16 models): the whole layer stack of a verification step as ONE persistent
 // kernel, and a second launch of the same kernel for the unembedding with fused arg-max.
 //
 // A step reads every weight once (13 GB at the 30-layer Mistral-7B shape) and computes almost
@@ -12,7 +12,7 @@
 //     runs ahead of the arithmetic by up to the size of the ring, across every grid barrier.
 //   * Waves 0..6 are CONSUMERS.  In a GEMM phase each takes every 7th k-tile of the CU's
 //     column tiles, reads the weight fragments from the ring (ds_read_b128), the activation
-//     fragments from L2, multiplies (MFMA 16x16x32 bf16, fp32 accumulate); the seven partial
+//     fragments from L2, multiplies (MFMA 16x16x32 f16, fp32 accumulate); the seven partial
 //     sums are added in a fixed tree through LDS and the epilogue of the GEMM runs on the
 //     finished tile.  The other phases (attention, operand preparation, arg-max) also run on
 //     the consumer waves.
@@ -25,14 +25,16 @@
 //     cache policy (sc1), so the barrier needs no cache flush or invalidate.
 //
 // Data layout
-//   weights      per CU c, per layer: [GEMM][pass][k-tile][tile-in-pass][lane][8] bf16.  Column
+//   weights      per CU c, per layer: [GEMM][pass][k-tile][tile-in-pass][lane][8] halves (the bf16
+//                weights convert to IEEE half precision without loss, see pack_f16).  Column
 //                tile t (16 columns) of a GEMM belongs to CU t mod G.  A fragment is the MFMA B
 //                operand of one k-tile (32 deep) x 16 columns: lane l holds column (l & 15),
 //                contraction indices 8 (l >> 4) .. +7; the direct-to-LDS load writes lane l's
 //                16 bytes at slot + 16 l, which is where the ds_read_b128 of lane l finds them.
-//   activations  [k-tile][row-tile][lane][8] bf16, the MFMA A operand, written by the epilogue
+//   activations  [k-tile][row-tile][lane][8] halves, the MFMA A operand, written by the epilogue
 //                that produces them, in buffers written once per launch (one per layer and
 //                use), so a reader can never find a stale copy in its L2.
+//   attention    q, K, V and the probabilities are bf16 (the KV cache is), on bf16 MFMA.
 //   RMSNorm      is applied as ((x * g) W) * rsqrt(mean(x^2) + eps): the row factor after the
 //                contraction, from per-tile sums of squares the O / down epilogues emit.
 // All reductions have a fixed order: results are run-to-run identical, and a row's result
