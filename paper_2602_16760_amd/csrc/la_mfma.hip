@@ -354,6 +354,22 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       for (int k = 0; k < 6; ++k) st[k] += (double)h[(size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * g + k] / f->n_wgs;
     fprintf(stderr, "[la trace]   producer (mean per workgroup): ring full %.1f times, %.1f polls; of %.1f us: draining before a poll %.1f us, "
             "polling for space %.1f us, waiting for the oldest chunk %.1f us\n", st[1], st[0], st[5] * 0.01, st[2] * 0.01, st[3] * 0.01, st[4] * 0.01);
+    {  // the producers at eight positions of one stretch of the stream (layer_stack: the gate / up weights of the second layer)
+      for (int g : {0, 1, 130}) {
+        if (g >= f->n_wgs) continue;
+        const unsigned long long *sa = &h[(size_t)TRACE_SLOTS * f->trace_phases + (size_t)TRACE_WG * g + 16];
+        if (!sa[7] || sa[7] <= sa[0]) continue;
+        fprintf(stderr, "[la trace]   producer of workgroup %d over the second layer's gate/up stream, per eighth: us (waiting oldest / polling / pacing):", g);
+        for (int k = 1; k < 8; ++k) {
+          auto w = [&](int i) { return (double)(sa[8 + i] & 0xffffffu); };
+          auto pl = [&](int i) { return (double)((sa[8 + i] >> 24) & 0xffffffu); };
+          auto pc = [&](int i) { return (double)((sa[8 + i] >> 48) & 0xffffu); };
+          fprintf(stderr, " %.1f (%.1f/%.1f/%.1f)", (sa[k] - sa[k - 1]) * 0.01, (w(k) - w(k - 1)) * 0.01, (pl(k) - pl(k - 1)) * 0.01,
+                  (pc(k) - pc(k - 1)) * 0.01);
+        }
+        fprintf(stderr, "\n");
+      }
+    }
     // when each workgroup reached the barrier that ends a phase, relative to the first one there
     for (int k = 0; k < 8 && a.trace_sel + k < np - 1; ++k) {
       const size_t base = (size_t)TRACE_SLOTS * f->trace_phases + 8 + k;
@@ -374,6 +390,13 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
               "by workgroup %% 8:", a.trace_sel + k, mean, (hi - lo) * 0.01, (h[base] - lo) * 0.01);
       for (int x = 0; x < 8; ++x) fprintf(stderr, " %.2f", nx[x] ? xcd[x] / nx[x] : 0.0);
       fprintf(stderr, "; first / second half of the grid: %.2f / %.2f\n", nh[0] ? half[0] / nh[0] : 0.0, nh[1] ? half[1] / nh[1] : 0.0);
+      if (env_int("LA_TRACE", 0) > 1) {  // every workgroup, one line per (workgroup % 8)
+        for (int x = 0; x < 8; ++x) {
+          fprintf(stderr, "[la trace]     %d:", x);
+          for (int g = x; g < f->n_wgs; g += 8) fprintf(stderr, " %.1f", (h[base + (size_t)TRACE_WG * g] - lo) * 0.01);
+          fprintf(stderr, "\n");
+        }
+      }
     }
   }
   return LA_OK;

@@ -69,7 +69,7 @@ constexpr unsigned OOB = 0x80000000u;      // voffset beyond every buffer (all a
 constexpr unsigned RSRC_BYTES = 0x7fffffffu;
 constexpr int DEV = 16;                    // cache policy sc1: device-scope coherent load / store
 constexpr int TRACE_SLOTS = 40;            // timestamps per phase of the optional timeline
-constexpr int TRACE_WG = 16;               // words per workgroup after the phases: 8 of the producer, 8 barrier arrival times
+constexpr int TRACE_WG = 32;               // words per workgroup after the phases: 8 of the producer, 8 barrier arrival times, 2 x 8 producer snapshots
 constexpr int NT_HINT = 2;                 // cache policy nt: streamed once
 constexpr int SYNC_GROUP = 16;             // workgroups per arrival counter of the grid barrier
 constexpr int SYNC_STRIDE = 64;            // 32-bit words between barrier variables (256 B)
@@ -392,7 +392,8 @@ __device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned
 // C_LANDED as chunks land, and never overwrites a slot before every consumer wave has moved
 // past the fragment it held.
 __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_AS uint8_t *ring, unsigned first_seg, unsigned n_seg,
-                                         unsigned seg_used, unsigned seg_stride, unsigned long long *stats) {
+                                         unsigned seg_used, unsigned seg_stride, unsigned long long *stats, unsigned snap_a,
+                                         unsigned snap_b) {
   const int lane = threadIdx.x & 63;
   const uint8_t *base = uni_ptr(a.wstream + (size_t)blockIdx.x * a.cu_bytes);
   __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(base), 0, uni((unsigned)a.cu_bytes), 0x00020000);
@@ -437,8 +438,18 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
   };
   unsigned idle_spins = 0;
   const unsigned pace = uni(a.pace);
-  unsigned long long t_issue = 0;
+  unsigned long long t_issue = 0, t_pace = 0;
+  snap_a = uni(snap_a);
+  snap_b = uni(snap_b);
+  int snaps = 0;
   while (next < total) {
+    if (tr && snaps < 8 && next >= snap_a + (unsigned)snaps * ((snap_b - snap_a) / 7)) {  // (timeline only) eight stream positions
+      if (lane == 0) {
+        stats[16 + snaps] = wall_clock64();
+        stats[24 + snaps] = ((unsigned long long)(t_wait & 0xffffffu)) | ((unsigned long long)(t_poll & 0xffffffu) << 24) | ((unsigned long long)(t_pace & 0xffffu) << 48);
+      }
+      ++snaps;
+    }
     if (next + CHUNK > free_until) {
       read_space();
       if (next + CHUNK > free_until) {
@@ -467,8 +478,10 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
       }
     }
     if (pace) {
+      const unsigned long long t0 = tr ? wall_clock64() : 0ull;
       while ((unsigned long long)clock64() - t_issue < pace) __builtin_amdgcn_s_sleep(1);
       t_issue = (unsigned long long)clock64();
+      if (tr) t_pace += wall_clock64() - t0;
     }
     {
       // a chunk is contiguous in memory and in the ring (segments are padded to whole chunks):
@@ -1372,8 +1385,10 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
 
   if (wave == NCW) {
     unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x : nullptr;
-    if (a.mode == 0) producer(a, ctl, lds + LDS_RING, (unsigned)a.lb, (unsigned)(a.le - a.lb), f_layer, a.seg_frags, st);
-    else producer(a, ctl, lds + LDS_RING, 0u, 1u, f_un, a.seg_frags, st);
+    // (timeline: producer snapshots at the start and the end of the second layer's gate / up weights)
+    const unsigned gu0 = f_layer + f_qkv + f_o;
+    if (a.mode == 0) producer(a, ctl, lds + LDS_RING, (unsigned)a.lb, (unsigned)(a.le - a.lb), f_layer, a.seg_frags, st, gu0, gu0 + f_gu);
+    else producer(a, ctl, lds + LDS_RING, 0u, 1u, f_un, a.seg_frags, st, ~0u, ~0u);
     return;
   }
 
