@@ -196,6 +196,21 @@ def main():
     per_step = {k: round(v[1] / 3.0, 4) for k, v in sorted(allk.items(), key=lambda kv: -kv[1][1])}
     log("per-step kernel ms (event-bracketed pass):", json.dumps(per_step))
 
+    # the same step with a one-row block (sequential decoding): the method's premise is that a
+    # 32-row verify step costs about what a one-token step costs (Section 4.2)
+    L_seq = int(st1.L) + 3 * N_LA
+    B.la_kv_set_len(eng.kv, L_seq)
+    eng.start(np.concatenate([prompt, prompt[: L_seq + 1 - len(prompt)]])[: L_seq + 1], 0, 1, 0, 1, seed_pool=False, prefill=False)
+    seq_emitted = torch.zeros(64, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        eng.step(seq_emitted, 64)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        eng.step(seq_emitted, 64)
+    torch.cuda.synchronize()
+    seq_ms = (time.perf_counter() - t0) * 1e3 / 20
+
     L_mid = (st0.L + st1.L) / 2.0
     step_bytes = algorithmic_bytes(shape, n_layers, L_mid, BP)
     gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
@@ -232,6 +247,8 @@ def main():
         "accepted_tok_per_step": round((st1.n_emitted - st0.n_emitted) / max(st1.steps - st0.steps, 1), 3),
         "emitted_tok_per_s": round((st1.n_emitted - st0.n_emitted) / dt, 1),
         "kernel_ms_per_step": per_step,
+        "one_row_step_ms": round(seq_ms, 4),
+        "block_to_one_row_latency_ratio": round(ms_per_step / seq_ms, 3),
         "roofline": {
             "bound": "hbm", "kernel": dominant, "achieved": round(dom_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
             "frac": round(dom_gbps / PEAK_HBM_GBPS, 4), "traffic": measured_traffic(),
