@@ -349,6 +349,14 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     if (np > 1 && h[S * (np - 1)] > h[0])
       fprintf(stderr, "[la trace]   shader clock over the launch: %.0f MHz\n",
               (double)(h[S * (np - 1) + 12] - h[12]) / ((h[S * (np - 1)] - h[0]) * 0.01));
+    if (np > 11 && (np - 1) % 5 == 0) {  // layer_stack: five phases a layer after the first one
+      fprintf(stderr, "[la trace]   per layer, us (shader clock, MHz):");
+      for (int l = 0; 5 * l + 6 < np; ++l) {
+        const unsigned long long *p0 = &h[(size_t)S * (5 * l + 1)], *p1 = &h[(size_t)S * (5 * l + 6)];
+        fprintf(stderr, " %.1f (%.0f)", (p1[0] - p0[0]) * 0.01, p1[0] > p0[0] ? (double)(p1[12] - p0[12]) / ((p1[0] - p0[0]) * 0.01) : 0.0);
+      }
+      fprintf(stderr, "\n");
+    }
     double st[6] = {0, 0, 0, 0, 0, 0};
     for (int g = 0; g < f->n_wgs; ++g)
       for (int k = 0; k < 6; ++k) st[k] += (double)h[(size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * g + k] / f->n_wgs;
