@@ -14,6 +14,13 @@ synchronisation; the state lives on the device.  Inputs are resident in HBM befo
 Prints one JSON line.  `value` = block rows verified per second.  `roofline` is measured
 with HIP events around the dominant kernel's launches during the timed steps;
 `cpu_baseline` times the float64 oracle on a bounded sample of the same workload.
+
+`--workload` runs the same measurement on the other BASELINE configurations (never the default,
+and never what `value` is quoted on): `config3` (24 layers, context 2048, 43-row block padded to
+48), `config4` (12B shape: 38 layers, hidden 5120, vocabulary 131072, context 4096, 32-row
+block), `config5` (all 32 layers of the 7B shape, 1024-token Markov prompt prefilled through
+the model, 512 tokens generated with lookahead and again one token at a time; `value` is then
+the emitted tokens per second of the lookahead run).
 """
 from __future__ import annotations
 
@@ -34,12 +41,19 @@ L0 = 512
 N_LAYERS = 30
 PEAK_HBM_GBPS = 8000.0
 
+# name -> (shape, layers, KV context, W, N, G, padded rows, description)
+WORKLOADS = {
+    "config2": ("mistral7b", 30, 512, 5, 4, 5, 32, "Mistral-7B-shape cloud share"),
+    "config3": ("mistral7b", 24, 2048, 7, 4, 7, 48, "Mistral-7B-shape cloud share"),
+    "config4": ("nemo12b", 38, 4096, 5, 4, 5, 32, "NeMo-12B-shape cloud share"),
+}
+
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
-def build_engine(shape, max_len, seed=0):
+def build_engine(shape, max_len, seed=0, kv_rows=L0):
     import torch
     import synth
     from paper_2602_16760_amd.engine import Engine
@@ -56,8 +70,8 @@ def build_engine(shape, max_len, seed=0):
             futs[l] = None
             if l % 5 == 4:
                 log(f"layer {l + 1}/{shape.n_layers} uploaded ({time.time() - t0:.0f} s)")
-    for l in range(shape.n_layers):
-        k, v = synth.kv_fill(shape, l, L0, seed)
+    for l in range(shape.n_layers if kv_rows else 0):
+        k, v = synth.kv_fill(shape, l, kv_rows, seed)
         eng.fill_kv(l, k, v)
     torch.cuda.synchronize()
     log(f"model + cache resident after {time.time() - t0:.0f} s")
@@ -74,8 +88,8 @@ def algorithmic_bytes(shape, n_layers, L, Bp):
     return n_layers * (per_layer + kv_read + kv_write) + unembed
 
 
-def cpu_baseline(shape):
-    """The oracle as it stands on the host cores: one layer of the 30, same block and cache."""
+def cpu_baseline(shape, n_layers, L, W, N, G, Bp):
+    """The oracle as it stands on the host cores: one layer of the stack, same block and cache."""
     import synth
     from oracle import lookahead as ola
     from oracle import transformer as otf
@@ -84,13 +98,12 @@ def cpu_baseline(shape):
     w = synth.layer_weights(sh1, 0, 0, True)
     om = otf.Model(sh1, lambda l: w, None, cache=True)
     om.layer(0)  # widen outside the timed region: it stands in for weights resident in memory
-    kv = otf.KVCache(sh1, L0 + BP, 1)
-    k, v = synth.kv_fill(sh1, 0, L0, 0)
+    kv = otf.KVCache(sh1, L + Bp, 1)
+    k, v = synth.kv_fill(sh1, 0, L, 0)
     kv.fill(0, k, v)
-    kv.L = L0
-    _, pos, vis = ola.build_block(0, L0, [[0] * W_LA for _ in range(N_LA - 1)], [(0,) * (N_LA - 1)] * G_LA,
-                                  W_LA, N_LA, G_LA, BP)
-    x = synth.hidden_block(sh1, BP, 0)
+    kv.L = L
+    _, pos, vis = ola.build_block(0, L, [[0] * W for _ in range(N - 1)], [(0,) * (N - 1)] * G, W, N, G, Bp)
+    x = synth.hidden_block(sh1, Bp, 0)
     # about ten seconds of oracle work: one warm-up pass, then as many passes as fit (at most 400)
     otf.forward_block(om, kv, x, pos, vis)
     reps, t0 = 0, time.time()
@@ -98,21 +111,21 @@ def cpu_baseline(shape):
         otf.forward_block(om, kv, x, pos, vis)
         reps += 1
     dt = (time.time() - t0) / reps
-    rows = ola.block_rows(W_LA, N_LA, G_LA)
+    rows = ola.block_rows(W, N, G)
     return {
-        "value": rows / (dt * N_LAYERS),
+        "value": rows / (dt * n_layers),
         "unit": "tok/s",
         "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
         "kind": "oracle",
-        "sample": f"1 of {N_LAYERS} layers (float64 numpy, {BP}-row block, L={L0}), {reps} repetitions, "
-                  f"{dt:.2f} s per layer, step time extrapolated x{N_LAYERS}; unembedding not included",
+        "sample": f"1 of {n_layers} layers (float64 numpy, {Bp}-row block, L={L}), {reps} repetitions, "
+                  f"{dt:.2f} s per layer, step time extrapolated x{n_layers}; unembedding not included",
     }
 
 
-def measured_traffic():
+def measured_traffic(workload):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size), or None."""
-    path = os.path.join(ROOT, "profiles", "layer_stack_config2_pmc.txt")
+    path = os.path.join(ROOT, "profiles", f"layer_stack_{workload}_pmc.txt")
     try:
         with open(path) as f:
             for line in f:
@@ -123,40 +136,36 @@ def measured_traffic():
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--layers", type=int, default=N_LAYERS, help=argparse.SUPPRESS)
-    ap.add_argument("--calib-copy", action="store_true",
-                    help="also launch a 1 GiB copy kernel (calib_copy) before the timed steps: a dispatch of known "
-                         "traffic for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+def quantiles(ms):
+    a = np.sort(np.asarray(ms, dtype=np.float64))
+    pick = lambda q: float(a[min(len(a) - 1, int(round(q * (len(a) - 1))))])
+    return {"p10": round(pick(0.10), 4), "median": round(pick(0.50), 4), "p90": round(pick(0.90), 4)}
 
+
+ARITHMETIC = ("bf16 weights and KV cache; the weight GEMMs multiply the weights as f16 (the conversion is exact) "
+              "with f16 activations and f32 accumulation; attention on bf16 MFMA; residual stream f32")
+
+
+def run_verify_steps(args):
+    """One block per step through the whole hot path, cache pre-filled with N(0, 1) rows."""
     import torch
     import synth
     from paper_2602_16760_amd import binding as B
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    n_layers = args.layers
-    shape = synth.SHAPES["mistral7b"].with_layers(n_layers)
-    rows = 1 + (W_LA + G_LA) * (N_LA - 1)
+    shape_name, n_layers, L_start, W, N, G, Bp, what = WORKLOADS[args.workload]
+    if args.layers is not None:
+        n_layers = args.layers
+    shape = synth.SHAPES[shape_name].with_layers(n_layers)
+    rows = 1 + (W + G) * (N - 1)
     total_steps = args.warmup + args.steps + 8
-    max_len = L0 + total_steps * N_LA + BP + 64
-    eng = build_engine(shape, max_len)
+    max_len = L_start + total_steps * N + Bp + 64
+    eng = build_engine(shape, max_len, kv_rows=L_start)
 
-    # controller: prompt of L0+1 synthetic "code-like" tokens seeds the pool; the cache rows
-    # 0..L0-1 are the N(0,1) fill, so nothing is prefilled through the model
-    prompt = synth.markov_prompt(shape.vocab, L0 + 1, 0.30, 0)
-    eng.start(prompt, W_LA, N_LA, G_LA, BP, seed_pool=True, prefill=False)
-    budget = total_steps * N_LA + 16
+    # controller: prompt of L_start+1 synthetic "code-like" tokens seeds the pool; the cache rows
+    # 0..L_start-1 are the N(0,1) fill, so nothing is prefilled through the model
+    prompt = synth.markov_prompt(shape.vocab, L_start + 1, 0.30, 0)
+    eng.start(prompt, W, N, G, Bp, seed_pool=True, prefill=False)
+    budget = total_steps * N + 16
     emitted = torch.zeros(budget, dtype=torch.int32, device="cuda")
 
     for _ in range(args.warmup):
@@ -174,10 +183,13 @@ def main():
     dominant = "layer_stack"   # the persistent kernel that runs all layers of the step
     B.la_profile_select(dominant)
     B.la_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # (the steps run on torch's current stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         eng.step(emitted, budget)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     B.la_profile_enable(False)
@@ -185,6 +197,7 @@ def main():
     B.la_profile_select(None)
     st1 = B.read_state(eng.state)
     ms_per_step = dt * 1e3 / args.steps
+    step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
 
     # attribution pass (not timed): every kernel bracketed
     B.la_profile_enable(True)
@@ -198,7 +211,7 @@ def main():
 
     # the same step with a one-row block (sequential decoding): the method's premise is that a
     # 32-row verify step costs about what a one-token step costs (Section 4.2)
-    L_seq = int(st1.L) + 3 * N_LA
+    L_seq = int(st1.L) + 3 * N
     B.la_kv_set_len(eng.kv, L_seq)
     eng.start(np.concatenate([prompt, prompt[: L_seq + 1 - len(prompt)]])[: L_seq + 1], 0, 1, 0, 1, seed_pool=False, prefill=False)
     seq_emitted = torch.zeros(64, dtype=torch.int32, device="cuda")
@@ -212,11 +225,11 @@ def main():
     seq_ms = (time.perf_counter() - t0) * 1e3 / 20
 
     L_mid = (st0.L + st1.L) / 2.0
-    step_bytes = algorithmic_bytes(shape, n_layers, L_mid, BP)
+    step_bytes = algorithmic_bytes(shape, n_layers, L_mid, Bp)
     gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
     launches, total_ms = prof.get(dominant, (0, 0.0))
     # per launch: every layer's weights once, every live KV row once, the block's KV written once
-    dom_bytes = int(algorithmic_bytes(shape, n_layers, L_mid, BP) - 2 * shape.d_model * shape.vocab)
+    dom_bytes = int(algorithmic_bytes(shape, n_layers, L_mid, Bp) - 2 * shape.d_model * shape.vocab)
     dom_ms = total_ms / max(launches, 1)
     dom_gbps = dom_bytes / (dom_ms * 1e-3) / 1e9 if dom_ms > 0 else 0.0
 
@@ -234,13 +247,14 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {
-            "workload": f"Mistral-7B-shape cloud share, {n_layers} layers, KV prefilled to {L0}, "
-                        f"{BP}-row lookahead block (W={W_LA}, N={N_LA}, G={G_LA}: {rows} rows + pad), batch 1, "
-                        "plus embedding gather, unembedding (vocab 32768) + arg-max, n-gram accept + KV commit",
-            "block_rows": BP, "kv_len_start": int(st0.L), "kv_len_end": int(st1.L),
-            "arithmetic": "bf16 weights and KV cache; the weight GEMMs multiply the weights as f16 (the conversion is exact) "
-                          "with f16 activations and f32 accumulation; attention on bf16 MFMA; residual stream f32",
+            "workload": f"{what}, {n_layers} layers, KV prefilled to {L_start}, "
+                        f"{Bp}-row lookahead block (W={W}, N={N}, G={G}: {rows} rows + pad), batch 1, "
+                        f"plus embedding gather, unembedding (vocab {shape.vocab}) + arg-max, n-gram accept + KV commit",
+            "name": args.workload,
+            "block_rows": Bp, "kv_len_start": int(st0.L), "kv_len_end": int(st1.L),
+            "arithmetic": ARITHMETIC,
         },
+        "step_ms_quantiles": quantiles(step_ms),
         "step_hbm_gbps": round(gbps, 1),
         "step_hbm_frac_peak": round(gbps / PEAK_HBM_GBPS, 4),
         "step_algorithmic_bytes": int(step_bytes),
@@ -251,15 +265,134 @@ def main():
         "block_to_one_row_latency_ratio": round(ms_per_step / seq_ms, 3),
         "roofline": {
             "bound": "hbm", "kernel": dominant, "achieved": round(dom_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-            "frac": round(dom_gbps / PEAK_HBM_GBPS, 4), "traffic": measured_traffic(),
+            "frac": round(dom_gbps / PEAK_HBM_GBPS, 4), "traffic": measured_traffic(args.workload),
             "bytes_per_launch": dom_bytes, "launches": launches, "avg_launch_ms": round(dom_ms, 5),
         },
     }
+    if args.workload != "config2":
+        out["metric"] = f"lookahead-step ms + verified tok/s + HBM GB/s % peak, {what}, {n_layers} layers ({args.workload})"
     if not args.no_cpu_baseline:
         log("timing the float64 oracle on one layer (host cores) ...")
-        out["cpu_baseline"] = cpu_baseline(shape)
+        out["cpu_baseline"] = cpu_baseline(shape, n_layers, L_start, W, N, G, Bp)
     eng.close()
     print(json.dumps(out), flush=True)
+
+
+def run_generation(args):
+    """BASELINE config 5: the prompt goes through the model, then 512 tokens are generated with
+    the lookahead controller and again one token per step; both streams come from the same
+    weights and cache contents, and are compared."""
+    import torch
+    import synth
+    from paper_2602_16760_amd import binding as B
+
+    W, N, G, Bp = W_LA, N_LA, G_LA, BP
+    n_prompt, n_new = 1024, 512
+    shape = synth.SHAPES["mistral7b"] if args.layers is None else synth.SHAPES["mistral7b"].with_layers(args.layers)
+    prompt = synth.markov_prompt(shape.vocab, n_prompt, 0.40, 1)
+    eng = build_engine(shape, n_prompt + n_new + 64, kv_rows=0)
+
+    def timed_generate(w, n, g, bp):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        eng.start(prompt, w, n, g, bp)  # prefill of prompt[:-1] in 64-row causal chunks + controller set-up
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        emitted = torch.zeros(n_new, dtype=torch.int32, device="cuda")
+        n_field = B.state_field(eng.state, "n_emitted")
+        done = 0
+        while done < n_new:  # (one host look at the device counter every eight steps, every step near the end)
+            for _ in range(8 if n_new - done > 8 * n else 1):
+                eng.step(emitted, n_new)
+            done = int(n_field.item())
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        st = B.read_state(eng.state)
+        return emitted.cpu().numpy().astype(np.int64), st, t1 - t0, t2 - t1
+
+    dominant = "layer_stack"
+    timed_generate(W, N, G, Bp)  # warm-up run
+    B.la_profile_select(dominant)
+    B.la_profile_enable(True)
+    la_toks, la_st, la_prefill_s, la_s = timed_generate(W, N, G, Bp)
+    B.la_profile_enable(False)
+    prof = B.la_profile_read()
+    B.la_profile_select(None)
+    seq_toks, seq_st, seq_prefill_s, seq_s = timed_generate(0, 1, 0, 1)
+    same = int((la_toks == seq_toks).sum())
+    log(f"lookahead {la_st.steps} steps / sequential {seq_st.steps} steps for {n_new} tokens; streams equal on {same}/{n_new}")
+
+    la_ms = la_s * 1e3 / la_st.steps
+    launches, total_ms = prof.get(dominant, (0, 0.0))
+    n_prefill_launches = (n_prompt - 1 + 63) // 64
+    L_mid = n_prompt + n_new / 2.0
+    dom_bytes = int(algorithmic_bytes(shape, shape.n_layers, L_mid, Bp) - 2 * shape.d_model * shape.vocab)
+    out = {
+        "metric": f"end-to-end greedy generation, Mistral-7B shape, all {shape.n_layers} layers (config5)",
+        "value": round(n_new / la_s, 1),
+        "unit": "emitted tok/s",
+        "n_gpus": 1,
+        "steps": int(la_st.steps),
+        "warmup": 1,
+        "ms_per_step": round(la_ms, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"Mistral-7B shape, {shape.n_layers} layers + embedding + unembedding (vocab {shape.vocab}); {n_prompt}-token "
+                        f"Markov prompt (40 % repeated spans) prefilled through the model in 64-row chunks; {n_new} tokens "
+                        f"generated with W={W}, N={N}, G={G} ({Bp}-row block) and again one token per step",
+            "name": "config5", "block_rows": Bp, "arithmetic": ARITHMETIC,
+        },
+        "lookahead": {"steps": int(la_st.steps), "tok_per_step": round(n_new / la_st.steps, 3),
+                      "steps_with_a_match": int(la_st.matched_steps), "seconds": round(la_s, 4), "tok_per_s": round(n_new / la_s, 1),
+                      "prefill_seconds": round(la_prefill_s, 4)},
+        "sequential": {"steps": int(seq_st.steps), "seconds": round(seq_s, 4), "tok_per_s": round(n_new / seq_s, 1),
+                       "ms_per_step": round(seq_s * 1e3 / seq_st.steps, 4), "prefill_seconds": round(seq_prefill_s, 4)},
+        "speedup_over_sequential": round(seq_s / la_s, 3),
+        "streams_equal_positions": same,
+        "roofline": {
+            "bound": "hbm", "kernel": dominant, "achieved": None, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": None,
+            "traffic": None, "bytes_per_launch": dom_bytes, "launches": launches,
+            "note": f"the {launches} launches include {n_prefill_launches} prefill launches of 64 rows",
+        },
+    }
+    if launches:
+        dom_ms = total_ms / launches
+        g = dom_bytes / (dom_ms * 1e-3) / 1e9
+        out["roofline"].update(achieved=round(g, 1), frac=round(g / PEAK_HBM_GBPS, 4), avg_launch_ms=round(dom_ms, 5))
+    eng.close()
+    print(json.dumps(out), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["config5"], default="config2",
+                    help="config2 (default) is the configuration the metric is quoted on")
+    ap.add_argument("--layers", type=int, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch a 1 GiB copy kernel (calib_copy) before the timed steps: a dispatch of known "
+                         "traffic for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    if args.workload == "config5":
+        run_generation(args)
+    else:
+        run_verify_steps(args)
 
 
 if __name__ == "__main__":
