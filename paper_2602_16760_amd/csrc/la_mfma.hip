@@ -446,7 +446,7 @@ static StackArgs base_stack_args(la_model *m, int Bp) {
   a.cs = m->rope_cs;
   a.sync = f->sync;
   a.dbg = env_int("LA_DBG", 0);
-  a.pace = (unsigned)env_int("LA_PACE", 600);
+  a.pace = (unsigned)env_int("LA_PACE", 700);
   a.qkv = dev_plan(f->p_qkv);
   a.o = dev_plan(f->p_o);
   a.gu = dev_plan(f->p_gu);

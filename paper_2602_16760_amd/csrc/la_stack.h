@@ -141,8 +141,9 @@ struct StackArgs {
   size_t cu_bytes;
   unsigned seg_frags;
   unsigned pace;  // shader-clock cycles a producer lets pass between two chunks (0: as fast as it can).
-                  // A little above the memory's share per CU: without it the producers' bursts after
-                  // every stall fill the memory queues, and the measured step is 1-2 % longer.
+                  // About the memory's share per CU (8 KB per 700 cycles at 2.4 GHz is 28 GB/s, times
+                  // 256 CUs 7.2 TB/s): 650-750 measure the same, 600 and none 1.5-2 % longer (the
+                  // producers' bursts after every stall fill the memory queues unevenly), 800 4 % longer.
   float *x;
   const int32_t *pos;
   const uint64_t *vis;
@@ -391,6 +392,7 @@ __device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned
 // chunks; seg_stride fragments apart in memory) into the ring, in order.  Keeps FLIGHT chunks in flight, publishes
 // C_LANDED as chunks land, and never overwrites a slot before every consumer wave has moved
 // past the fragment it held.
+template <bool TR>  // TR: with the timeline's clock reads and counters (the untraced loop holds none of them)
 __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_AS uint8_t *ring, unsigned first_seg, unsigned n_seg,
                                          unsigned seg_used, unsigned seg_stride, unsigned long long *stats, unsigned snap_a,
                                          unsigned snap_b) {
@@ -407,7 +409,7 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
   unsigned seg_off = first_seg * seg_stride, f_in_seg = 0;  // memory position of fragment `next`
   unsigned polls = 0, full_events = 0;
   unsigned long long t_wait = 0, t_poll = 0;
-  const bool tr = stats != nullptr;
+  constexpr bool tr = TR;
   const unsigned long long t_begin = tr ? wall_clock64() : 0ull;
   if (a.dbg & 1) {
     ctl_write(ctl + 4 * C_LANDED, total);
@@ -431,14 +433,19 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
   };
   auto read_space = [&]() {
     const unsigned c = ctl_read_lanes(ctl + 4 * (C_PROG + (lane < NCW ? lane : 0)));
-    unsigned m = (unsigned)__builtin_amdgcn_readlane((int)c, 0);
-#pragma unroll
-    for (int k = 1; k < NCW; ++k) m = min(m, (unsigned)__builtin_amdgcn_readlane((int)c, k));
-    free_until = m + NSLOT;
+    // minimum of lanes 0..7 (lane 7 holds wave 0's word again) in three steps within the row:
+    // after the shifts by 1, 2 and 4 lanes, lane 7 has seen lanes 0..7
+    unsigned m = c;
+    m = min(m, (unsigned)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x111, 0xf, 0xf, false));
+    m = min(m, (unsigned)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x112, 0xf, 0xf, false));
+    m = min(m, (unsigned)__builtin_amdgcn_update_dpp((int)m, (int)m, 0x114, 0xf, 0xf, false));
+    static_assert(NCW == 7, "eight lanes: seven waves and one repeat");
+    free_until = (unsigned)__builtin_amdgcn_readlane((int)m, 7) + NSLOT;
   };
   unsigned idle_spins = 0;
   const unsigned pace = uni(a.pace);
-  unsigned long long t_issue = 0, t_pace = 0;
+  unsigned long long t_pace = 0;
+  unsigned t_next = (unsigned)clock64();  // (the clock's low word: differences are taken modulo 2^32)
   snap_a = uni(snap_a);
   snap_b = uni(snap_b);
   int snaps = 0;
@@ -479,8 +486,12 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
     }
     if (pace) {
       const unsigned long long t0 = tr ? wall_clock64() : 0ull;
-      while ((unsigned long long)clock64() - t_issue < pace) __builtin_amdgcn_s_sleep(1);
-      t_issue = (unsigned long long)clock64();
+      unsigned now = (unsigned)clock64();
+      while ((int)(now - t_next) < 0) {
+        __builtin_amdgcn_s_sleep(1);
+        now = (unsigned)clock64();
+      }
+      t_next = now + pace;
       if (tr) t_pace += wall_clock64() - t0;
     }
     {
@@ -1384,11 +1395,14 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   const unsigned f_un = ((unsigned)(my_tiles(a.un.ntiles) * a.un.KT) + CHUNK - 1) / CHUNK * CHUNK;
 
   if (wave == NCW) {
+    __builtin_amdgcn_s_setprio(3);  // the producer's few instructions go first on its SIMD (4 % on a one-row step)
     unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x : nullptr;
     // (timeline: producer snapshots at the start and the end of the second layer's gate / up weights)
     const unsigned gu0 = f_layer + f_qkv + f_o;
-    if (a.mode == 0) producer(a, ctl, lds + LDS_RING, (unsigned)a.lb, (unsigned)(a.le - a.lb), f_layer, a.seg_frags, st, gu0, gu0 + f_gu);
-    else producer(a, ctl, lds + LDS_RING, 0u, 1u, f_un, a.seg_frags, st, ~0u, ~0u);
+    const unsigned first_seg = a.mode == 0 ? (unsigned)a.lb : 0u, n_seg = a.mode == 0 ? (unsigned)(a.le - a.lb) : 1u;
+    const unsigned seg_used = a.mode == 0 ? f_layer : f_un;
+    if (st) producer<true>(a, ctl, lds + LDS_RING, first_seg, n_seg, seg_used, a.seg_frags, st, a.mode == 0 ? gu0 : ~0u, a.mode == 0 ? gu0 + f_gu : ~0u);
+    else producer<false>(a, ctl, lds + LDS_RING, first_seg, n_seg, seg_used, a.seg_frags, nullptr, ~0u, ~0u);
     return;
   }
 
