@@ -37,6 +37,9 @@ CASES = [
     ("small_bf16", 2, 515, (7, 4, 7), 48, 7),
     ("small_bf16", 1, 31, (0, 1, 0), 1, 0),       # sequential step: one row
     ("small64_bf16", 2, 77, (4, 3, 4), 17, 4),    # head_dim 64, odd row count
+    ("small_bf16", 2, 0, (5, 4, 5), 32, 0),       # empty cache on the matrix-core path: only this step's rows are keys
+    ("small_bf16", 2, 96, (10, 4, 11), 64, 11),   # the largest block (64 rows, four row tiles), cache a whole number of key blocks
+    ("small64_bf16", 1, 1, (3, 2, 2), 6, 1),      # one cached row
 ]
 
 
@@ -67,6 +70,30 @@ def test_forward_layers_matches_oracle(name, nl, L, wng, Bp, n_cand):
         prefill_both(shape, eng, okv, L, seed=4)
         again = eng.forward(x, pos, vis)
         assert np.array_equal(got, again)
+    finally:
+        eng.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
+def test_layer_ranges_compose(name):
+    """Layers [0, 1) then [1, n) in two calls give bit for bit what [0, n) gives in one (the paper's
+    split of the stack between two machines, Section 4.1, is a split of this call)."""
+    shape = synth.SHAPES[name]
+    nl, L, Bp = shape.n_layers, 70, 32
+    eng = gpu_engine(shape, L + Bp, seed=3, head=False)
+    try:
+        okv = otf.KVCache(shape, L + Bp)
+        prefill_both(shape, eng, okv, L, seed=4)
+        x, pos, vis = _block_inputs(shape, L, 5, 4, 5, Bp, 2, seed=6)
+        whole = eng.forward(x, pos, vis)
+        kv_whole = [eng.read_kv(l, L, Bp) for l in range(nl)]
+        prefill_both(shape, eng, okv, L, seed=4)
+        part = eng.forward(x, pos, vis, 0, 1)
+        part = eng.forward(part, pos, vis, 1, nl)
+        assert np.array_equal(whole, part)
+        for l in range(nl):
+            k, v = eng.read_kv(l, L, Bp)
+            assert np.array_equal(k, kv_whole[l][0]) and np.array_equal(v, kv_whole[l][1])
     finally:
         eng.close()
 
