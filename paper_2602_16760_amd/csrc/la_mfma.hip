@@ -311,6 +311,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
   a.trace = f->trace;
   a.trace_phases = f->trace_phases;
   a.trace_sel = env_int("LA_TRACE_SEL", 6);
+  a.trace_seg = env_int("LA_TRACE_SEG", 2);
   int rc;
   {
     ProfScope ps(name, s);
@@ -363,17 +364,29 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     fprintf(stderr, "[la trace]   producer (mean per workgroup): ring full %.1f times, %.1f polls; of %.1f us: draining before a poll %.1f us, "
             "polling for space %.1f us, waiting for the oldest chunk %.1f us\n", st[1], st[0], st[5] * 0.01, st[2] * 0.01, st[3] * 0.01, st[4] * 0.01);
     {  // the producers at eight positions of one stretch of the stream (layer_stack: the gate / up weights of the second layer)
-      for (int g : {0, 1, 130}) {
+      for (int g : {0, 1, 130, env_int("LA_TRACE_WG", 130)}) {
         if (g >= f->n_wgs) continue;
         const unsigned long long *sa = &h[(size_t)TRACE_SLOTS * f->trace_phases + (size_t)TRACE_WG * g + 16];
         if (!sa[7] || sa[7] <= sa[0]) continue;
-        fprintf(stderr, "[la trace]   producer of workgroup %d over the second layer's gate/up stream, per eighth: us (waiting oldest / polling / pacing):", g);
+        fprintf(stderr, "[la trace]   producer of workgroup %d over one weight matrix of the second layer (LA_TRACE_SEG: 0 QKV, 1 O, 2 gate/up, 3 down), per eighth: us (waiting oldest / polling / pacing):", g);
         for (int k = 1; k < 8; ++k) {
           auto w = [&](int i) { return (double)(sa[8 + i] & 0xffffffu); };
           auto pl = [&](int i) { return (double)((sa[8 + i] >> 24) & 0xffffffu); };
           auto pc = [&](int i) { return (double)((sa[8 + i] >> 48) & 0xffffu); };
           fprintf(stderr, " %.1f (%.1f/%.1f/%.1f)", (sa[k] - sa[k - 1]) * 0.01, (w(k) - w(k - 1)) * 0.01, (pl(k) - pl(k - 1)) * 0.01,
                   (pc(k) - pc(k - 1)) * 0.01);
+        }
+        fprintf(stderr, "\n");
+      }
+    }
+    if (env_int("LA_TRACE", 0) > 1) {  // every producer: when it reached the traced matrix's end, and how long the matrix took it
+      unsigned long long lo = ~0ull;
+      for (int g = 0; g < f->n_wgs; ++g) lo = std::min(lo, h[(size_t)TRACE_SLOTS * f->trace_phases + (size_t)TRACE_WG * g + 16 + 7]);
+      for (int x = 0; x < 8; ++x) {
+        fprintf(stderr, "[la trace]     producers %d (end after the first / duration of the last three quarters, us):", x);
+        for (int g = x; g < f->n_wgs; g += 8) {
+          const unsigned long long *sa = &h[(size_t)TRACE_SLOTS * f->trace_phases + (size_t)TRACE_WG * g + 16];
+          fprintf(stderr, " %.1f/%.1f", (sa[7] - lo) * 0.01, (sa[7] - sa[2]) * 0.01);
         }
         fprintf(stderr, "\n");
       }

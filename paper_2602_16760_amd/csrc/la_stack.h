@@ -165,6 +165,7 @@ struct StackArgs {
   unsigned epoch0, n_groups;
   unsigned long long *trace;  // optional: per phase TRACE_SLOTS timestamps of workgroup 0, then TRACE_WG words per workgroup
   int trace_phases;
+  int trace_seg;              // which weight matrix of the second layer the producer's eight snapshots cover (0 QKV, 1 O, 2 gate / up, 3 down)
   int trace_sel;              // every workgroup records when it reaches the barriers that end phases trace_sel .. trace_sel + 7
 };
 
@@ -1398,10 +1399,13 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
     __builtin_amdgcn_s_setprio(3);  // the producer's few instructions go first on its SIMD (4 % on a one-row step)
     unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x : nullptr;
     // (timeline: producer snapshots at the start and the end of the second layer's gate / up weights)
-    const unsigned gu0 = f_layer + f_qkv + f_o;
+    // (timeline: which of the second layer's four weight matrices the snapshots cover: 0 QKV, 1 O, 2 gate / up, 3 down)
+    const unsigned seg0 = a.trace_seg == 0 ? 0u : a.trace_seg == 1 ? f_qkv : a.trace_seg == 3 ? f_qkv + f_o + f_gu : f_qkv + f_o;
+    const unsigned seg_n = a.trace_seg == 0 ? f_qkv : a.trace_seg == 1 ? f_o : a.trace_seg == 3 ? f_down : f_gu;
+    const unsigned gu0 = f_layer + seg0;
     const unsigned first_seg = a.mode == 0 ? (unsigned)a.lb : 0u, n_seg = a.mode == 0 ? (unsigned)(a.le - a.lb) : 1u;
     const unsigned seg_used = a.mode == 0 ? f_layer : f_un;
-    if (st) producer<true>(a, ctl, lds + LDS_RING, first_seg, n_seg, seg_used, a.seg_frags, st, a.mode == 0 ? gu0 : ~0u, a.mode == 0 ? gu0 + f_gu : ~0u);
+    if (st) producer<true>(a, ctl, lds + LDS_RING, first_seg, n_seg, seg_used, a.seg_frags, st, a.mode == 0 ? gu0 : ~0u, a.mode == 0 ? gu0 + seg_n : ~0u);
     else producer<false>(a, ctl, lds + LDS_RING, first_seg, n_seg, seg_used, a.seg_frags, nullptr, ~0u, ~0u);
     return;
   }
@@ -1447,6 +1451,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
     uint16_t *attn_l = a.attn_a + (size_t)layer * a.attn_stride, *act_l = a.act_a + (size_t)layer * a.act_stride;
     PassArgs p{};
     p.tr = tr;
+
     GemmDev g{};
     bool have_g = false;
     unsigned frags = 0;
