@@ -16,7 +16,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblookahead.so")
 
 SOURCES = ["la_api.hip", "la_generic.hip", "la_accept.hip", "la_mfma.hip",
-           "la_stack_mt1.hip", "la_stack_mt2.hip", "la_stack_mt3.hip", "la_stack_mt4.hip"]
+           "la_stack_mt1.hip", "la_stack_mt2.hip", "la_stack_mt3.hip", "la_stack_mt4.hip",
+           "la_rstack_mt1.hip", "la_rstack_mt2.hip", "la_rstack_mt3.hip", "la_rstack_mt4.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -5,9 +5,17 @@
 #include <algorithm>
 #include <new>
 
-#include "la_stack.h"
+#include "la_rstack.h"
 
 namespace la {
+
+namespace rs {
+extern template int launch_rstack_kernel<1, 4>(const StackArgs &, int, hipStream_t);
+extern template int launch_rstack_kernel<2, 4>(const StackArgs &, int, hipStream_t);
+extern template int launch_rstack_kernel<3, 4>(const StackArgs &, int, hipStream_t);
+extern template int launch_rstack_kernel<4, 4>(const StackArgs &, int, hipStream_t);
+}  // namespace rs
+constexpr int R_NW = 4;  // MFMA waves of the register-streaming kernel
 
 extern template int launch_stack_kernel<1>(const StackArgs &, int, hipStream_t);
 extern template int launch_stack_kernel<2>(const StackArgs &, int, hipStream_t);
@@ -55,6 +63,7 @@ struct PackDst {
   int G;
   int prev_ntiles[3], prev_KT[3], n_prev;
   int ntiles, KT, ntp;
+  int r_nw;  // 0: layout of the LDS-ring kernel (la_stack.h); else the register-streaming kernel's, for that many MFMA waves
 };
 
 __global__ void pack_weights_kernel(PackSrc p, PackDst d) {
@@ -73,7 +82,15 @@ __global__ void pack_weights_kernel(PackSrc p, PackDst d) {
       int pn = d.prev_ntiles[i] > c ? (d.prev_ntiles[i] - c + d.G - 1) / d.G : 0;
       off += (size_t)pn * d.prev_KT[i];
     }
-    off += (size_t)pass * d.ntp * d.KT + (size_t)kt * n_pass + tp;
+    if (d.r_nw) {
+      // per MFMA wave w: [its k-tiles w, w + NW, ...][all column tiles of this CU]
+      int w = kt % d.r_nw, i = kt / d.r_nw;
+      size_t before = 0;  // k-tiles of the waves in front of w
+      for (int v = 0; v < w; ++v) before += d.KT > v ? (d.KT - v + d.r_nw - 1) / d.r_nw : 0;
+      off += (before + i) * nt + lt;
+    } else {
+      off += (size_t)pass * d.ntp * d.KT + (size_t)kt * n_pass + tp;
+    }
     int pc = tile * 16 + (lane & 15);
     int k0 = kt * 32 + 8 * (lane >> 4);
     int ld;
@@ -109,6 +126,7 @@ struct GemmPlan {
 
 struct MfmaModel {
   int n_wgs = 256;
+  bool use_r = true;  // the register-streaming kernel (la_rstack.h); false: the LDS-ring kernel (la_stack.h)
   GemmPlan p_qkv, p_o, p_gu, p_down, p_un;
   uint8_t *wstream = nullptr;   // [CU][layer][seg_frags][1 KB]
   size_t cu_bytes = 0;
@@ -182,6 +200,7 @@ int mfma_create(la_model *m) {
   LA_HIP(hipGetDeviceProperties(&prop, m->device));
   int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   f->n_wgs = std::max(1, std::min(env_int("LA_WGS", cus), cus));  // one resident workgroup per CU: the barrier needs co-residency
+  f->use_r = env_int("LA_LDS_RING", 0) == 0;
   LA_REQUIRE((size_t)prop.sharedMemPerBlockOptin >= (size_t)LDS_BYTES || (size_t)prop.maxSharedMemoryPerMultiProcessor >= (size_t)LDS_BYTES,
              LA_EINVAL, "the device offers less LDS per workgroup than the %d bytes the kernel needs", LDS_BYTES);
   int qd = m->qdim(), nqkv = m->nqkv(), g = d.n_q_heads / d.n_kv_heads;
@@ -265,6 +284,7 @@ int mfma_set_layer(la_model *m, int layer, const la_layer_weights *w, hipStream_
     dst.ntiles = plans[gi]->ntiles;
     dst.KT = plans[gi]->KT;
     dst.ntp = plans[gi]->ntp;
+    dst.r_nw = f->use_r ? R_NW : 0;
     int rc = pack(srcs[gi], dst, s);
     if (rc) return rc;
   }
@@ -288,6 +308,7 @@ int mfma_set_head(la_model *m, const void *unembed, hipStream_t s) {
   dst.ntiles = f->p_un.ntiles;
   dst.KT = f->p_un.KT;
   dst.ntp = f->p_un.ntp;
+  dst.r_nw = f->use_r ? R_NW : 0;
   int rc = pack(u, dst, s);
   if (rc) return rc;
   // partial arg-max records per CU: one per reduction chunk of every pass, at any row count
@@ -315,11 +336,20 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
   int rc;
   {
     ProfScope ps(name, s);
-    switch (a.MT) {
-    case 1: rc = launch_stack_kernel<1>(a, f->n_wgs, s); break;
-    case 2: rc = launch_stack_kernel<2>(a, f->n_wgs, s); break;
-    case 3: rc = launch_stack_kernel<3>(a, f->n_wgs, s); break;
-    default: rc = launch_stack_kernel<4>(a, f->n_wgs, s); break;
+    if (f->use_r) {
+      switch (a.MT) {
+      case 1: rc = rs::launch_rstack_kernel<1, R_NW>(a, f->n_wgs, s); break;
+      case 2: rc = rs::launch_rstack_kernel<2, R_NW>(a, f->n_wgs, s); break;
+      case 3: rc = rs::launch_rstack_kernel<3, R_NW>(a, f->n_wgs, s); break;
+      default: rc = rs::launch_rstack_kernel<4, R_NW>(a, f->n_wgs, s); break;
+      }
+    } else {
+      switch (a.MT) {
+      case 1: rc = launch_stack_kernel<1>(a, f->n_wgs, s); break;
+      case 2: rc = launch_stack_kernel<2>(a, f->n_wgs, s); break;
+      case 3: rc = launch_stack_kernel<3>(a, f->n_wgs, s); break;
+      default: rc = launch_stack_kernel<4>(a, f->n_wgs, s); break;
+      }
     }
   }
   if (rc) return rc;
@@ -331,7 +361,8 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     const int S = TRACE_SLOTS;
     fprintf(stderr, "[la trace] %s: %d phases, total %.1f us (times below: us after the phase's start, workgroup 0 wave 0)\n", name, np,
             (h[S * (np - 1) + 2] - h[0]) * 0.01);
-    for (int q = 0; q < np && q < 12; ++q) {
+    for (int q = 0; q < np; ++q) {
+      if (q >= 12 && !(env_int("LA_TRACE", 0) > 2 && q >= np - 6)) continue;
       const unsigned long long t0 = h[S * q];
       auto rel = [&](int k) { return h[S * q + k] > t0 ? (h[S * q + k] - t0) * 0.01 : -1.0; };
       double since_prev = q > 0 ? (t0 - h[S * (q - 1) + 2]) * 0.01 : 0.0;
@@ -347,6 +378,33 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
         fprintf(stderr, "[la trace]             attention loop of wave 0: %d key blocks in %.2f us, of which %.2f us waiting for them\n",
                 (int)h[S * q + 14], h[S * q + 15] * 0.01, h[S * q + 13] * 0.01);
     }
+    if (f->use_r) fprintf(stderr, "[la trace]   kernel entry %.1f us, schedules written %.1f us before the first phase\n", (double)(long long)(h[0] - h[13]) * 0.01, (double)(long long)(h[0] - h[14]) * 0.01);
+    if (f->use_r) {
+      fprintf(stderr, "[la trace]   waves end, us after the first phase (workgroup 0, then workgroup 200):");
+      for (int k = 0; k < 16; ++k) fprintf(stderr, " %.1f", (double)(long long)(h[16 + k] - h[0]) * 0.01);
+      fprintf(stderr, "\n");
+    }
+    if (f->use_r) {
+      unsigned long long hi = 0; int who = -1, wv = -1;
+      for (int g = 3; g < f->n_wgs; ++g)
+        for (int k = 0; k < 8; ++k) {
+          unsigned long long t = h[(size_t)TRACE_SLOTS * f->trace_phases + (size_t)TRACE_WG * g + k];
+          if (t > hi) { hi = t; who = g; wv = k; }
+        }
+      fprintf(stderr, "[la trace]   last wave to end: workgroup %d wave %d, %.1f us after the first phase; ends of the last workgroups' waves:", who, wv, (double)(long long)(hi - h[0]) * 0.01);
+      for (int g = std::max(1, f->n_wgs - 3); g < f->n_wgs; ++g)
+        for (int k = 0; k < 8; ++k) fprintf(stderr, " %.0f", (double)(long long)(h[(size_t)TRACE_SLOTS * f->trace_phases + (size_t)TRACE_WG * g + k] - h[0]) * 0.01);
+      fprintf(stderr, "\n");
+    }
+    if (f->use_r && np > 11) {  // register-streaming kernel: when the MFMA waves of workgroup 0 started each body of the second layer
+      const unsigned long long *mw = &h[(size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG];
+      const unsigned t0 = (unsigned)h[(size_t)TRACE_SLOTS * 6];  // (start of the second layer's first phase)
+      for (int w = 0; w < 4; ++w) {
+        fprintf(stderr, "[la trace]   MFMA wave %d, second layer, start of its bodies, us after the layer's first phase began:", w);
+        for (int e = 0; e < 16; ++e) fprintf(stderr, " %.1f", (double)(int)((unsigned)mw[16 * w + e] - t0) * 0.01);
+        fprintf(stderr, "\n");
+      }
+    }
     if (np > 1 && h[S * (np - 1)] > h[0])
       fprintf(stderr, "[la trace]   shader clock over the launch: %.0f MHz\n",
               (double)(h[S * (np - 1) + 12] - h[12]) / ((h[S * (np - 1)] - h[0]) * 0.01));
@@ -356,6 +414,11 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
         const unsigned long long *p0 = &h[(size_t)S * (5 * l + 1)], *p1 = &h[(size_t)S * (5 * l + 6)];
         fprintf(stderr, " %.1f (%.0f)", (p1[0] - p0[0]) * 0.01, p1[0] > p0[0] ? (double)(p1[12] - p0[12]) / ((p1[0] - p0[0]) * 0.01) : 0.0);
       }
+      fprintf(stderr, "\n");
+    }
+    if (env_int("LA_TRACE", 0) > 2) {  // every phase: start after the launch's first mark, duration up to its last mark
+      fprintf(stderr, "[la trace]   every phase, start (us):");
+      for (int q = 0; q < np; ++q) fprintf(stderr, " %.1f", (h[S * q] - h[0]) * 0.01);
       fprintf(stderr, "\n");
     }
     double st[6] = {0, 0, 0, 0, 0, 0};

@@ -1,0 +1,7 @@
+// The register-streaming persistent kernel (la_rstack.h) for blocks of 33..48 rows (3 row tiles).
+#include "la_rstack.h"
+namespace la {
+namespace rs {
+template int launch_rstack_kernel<3, 4>(const StackArgs &, int, hipStream_t);
+}
+}  // namespace la
