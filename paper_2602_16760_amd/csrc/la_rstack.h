@@ -48,9 +48,14 @@ struct Geo {
   static constexpr int NTMAX = MT <= 2 ? 8 : 4;                       // column tiles per pass
   static constexpr int LDTMAX = 16 * NTMAX + 4;                       // padded row length of a partial tile (floats)
   static constexpr int PART_BYTES = 16 * MT * LDTMAX * 4;             // one wave's partial tile
-  static constexpr int RS = MT == 1 ? 32 : MT == 2 ? 16 : 8;  // operand ring: k-tiles per MFMA wave
+};
+// One MFMA wave's LDS region: its operand ring (RS k-tiles, a multiple of the loader's batch), which
+// is also where it leaves its partial tile.  Sized so that NW regions fit beside the rest.
+template <int MT, int NW>
+struct Lay {
+  static constexpr int RS = NW <= 4 ? (MT == 1 ? 32 : MT == 2 ? 16 : 8) : (MT == 1 ? 16 : MT == 2 ? 8 : 4);
   static constexpr int RING_BYTES = RS * MT * 1024;
-  static constexpr int REG = ((PART_BYTES > RING_BYTES ? PART_BYTES : RING_BYTES) + 1023) / 1024 * 1024;
+  static constexpr int REG = ((Geo<MT>::PART_BYTES > RING_BYTES ? Geo<MT>::PART_BYTES : RING_BYTES) + 1023) / 1024 * 1024;
 };
 
 // LDS map: NW regions (operand ring / partial tile of each MFMA wave), then the small stuff.
@@ -64,7 +69,7 @@ constexpr int M_X = 1280;      // this workgroup's columns of x: [column tile][r
 constexpr int X_BYTES = 4096;
 constexpr int M_BYTES = M_X + X_BYTES;
 template <int MT, int NW>
-constexpr int lds_bytes() { return NW * Geo<MT>::REG + M_BYTES + NW * (16 + 128 * 20) + 256; }    // (regions, small stuff, schedule tables, timeline of MFMA wave 0)
+constexpr int lds_bytes() { return NW * Lay<MT, NW>::REG + M_BYTES + NW * (16 + 128 * 20) + 256; }    // (regions, small stuff, schedule tables, timeline of MFMA wave 0)
 
 // control words (32-bit, at M_CTL)
 constexpr int K_DEAD = 0;      // a wait timed out: every wave leaves the kernel
@@ -318,11 +323,11 @@ __device__ __forceinline__ unsigned m_wait_ge(unsigned ctl, int word, unsigned w
 // The operand is read from LDS for four slots at a time (one fragment set per slot, the same one
 // several times when the slots share a k-tile): one look at the landing counter and one LDS
 // latency per four slots.
-template <int MT>
+template <int MT, int NW>
 __device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT][Geo<MT>::NTMAX], u32x4 rsrc, unsigned lane16, unsigned mask, int lg,
                                           unsigned a_seq, unsigned ctl, unsigned region, int w, unsigned next_mask, unsigned next_frag,
                                           unsigned next_stride, int next_lg) {
-  constexpr int RS = Geo<MT>::RS, AM = Geo<MT>::NTMAX - 1;
+  constexpr int RS = Lay<MT, NW>::RS, AM = Geo<MT>::NTMAX - 1;
   constexpr int GQ = MT <= 3 ? 4 : 2;  // slots per operand fetch (GQ x MT fragments in registers)
   unsigned seen = 0;  // operand k-tiles known to have landed (sequence number + 1)
   u32x4 av[GQ][MT];
@@ -411,10 +416,10 @@ __device__ __forceinline__ void dump_partial(const f32x4 (&acc)[MT][Geo<MT>::NTM
 template <int MT, int NW>
 __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0, int w, int lane) {
   constexpr int NTMAX = Geo<MT>::NTMAX;
-  const unsigned misc = lds0 + NW * Geo<MT>::REG;
+  const unsigned misc = lds0 + NW * Lay<MT, NW>::REG;
   const unsigned ctl = misc + M_CTL;
   const unsigned tab = misc + M_BYTES + (unsigned)w * TAB_BYTES;
-  const unsigned region = lds0 + (unsigned)w * Geo<MT>::REG;
+  const unsigned region = lds0 + (unsigned)w * Lay<MT, NW>::REG;
   const unsigned lane16 = (unsigned)lane * 16u;
   // buffer resource over this CU's stream
   const uint64_t base = (uint64_t)(a.wstream + (size_t)blockIdx.x * a.cu_bytes);
@@ -470,7 +475,7 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
       const int nlg = (int)((nw3 >> 16) & 0xffu);
       const bool last = (w4 & 1u) != 0;
       const unsigned pseq = (unsigned)l * p_per_layer + (w4 >> 16);
-      mfma_body<MT>(ring, acc, rsrc, lane16, uni(ent_word(e, 0)), lg, a_seq, ctl, region, w, nm, nf, nst, nlg);
+      mfma_body<MT, NW>(ring, acc, rsrc, lane16, uni(ent_word(e, 0)), lg, a_seq, ctl, region, w, nm, nf, nst, nlg);
       if (last) {
         // the pass is done for this wave: partial tile to LDS (its operand ring is idle now), tell the IO waves
         dump_partial<MT>(acc, lg, region, lane);
@@ -567,7 +572,7 @@ __device__ __forceinline__ bool io_grid_sync(const StackArgs &a, Io &io, unsigne
 // loop costs about half a microsecond of scalar code whatever it moves.)
 template <int MT, int NW>
 __device__ __forceinline__ bool load_operand(Io &io, const uint16_t *A, int KT, unsigned (&a_seq)[NW / (8 - NW)], int dbg) {
-  constexpr int NIO = 8 - NW, SV = NW / NIO, RS = Geo<MT>::RS, GB = 4, LPB = GB * SV * MT;
+  constexpr int NIO = 8 - NW, SV = NW / NIO, RS = Lay<MT, NW>::RS, GB = 4, LPB = GB * SV * MT;
   constexpr int FL0 = RS / GB < 63 / LPB + 1 ? RS / GB : 63 / LPB + 1;  // batches in flight: (FL - 1) LPB loads must fit the counter
   constexpr int FL = FL0 < 8 ? FL0 : 8;
   static_assert(RS % GB == 0 && FL >= 1 && (FL - 1) * LPB <= 63, "ring and load counter");
@@ -644,7 +649,7 @@ __device__ __forceinline__ bool load_operand(Io &io, const uint16_t *A, int KT, 
         const bool valid = i < nk[s];
         const int kt = w + NW * i;
         const unsigned slot = (a_seq[s] + (unsigned)g) % (unsigned)RS;
-        const unsigned dst = uni(io.lds0 + (unsigned)w * Geo<MT>::REG + slot * (MT * 1024u));
+        const unsigned dst = uni(io.lds0 + (unsigned)w * Lay<MT, NW>::REG + slot * (MT * 1024u));
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (LDS_AS void *)(uintptr_t)(dst + mt * 1024u), 16, (valid && !(dbg & 4)) ? voff : OOB,
@@ -887,7 +892,7 @@ __device__ __forceinline__ bool io_pass(const StackArgs &a, Io &io, const Pass &
     for (int i = io.tid; i < n4; i += NT_IO) {
       f32x4 s = t0[i];
 #pragma unroll
-      for (int w = 1; w < NW; ++w) s += *(LDS_AS const f32x4 *)(uintptr_t)(io.lds0 + (unsigned)w * Geo<MT>::REG + (unsigned)i * 16u);
+      for (int w = 1; w < NW; ++w) s += *(LDS_AS const f32x4 *)(uintptr_t)(io.lds0 + (unsigned)w * Lay<MT, NW>::REG + (unsigned)i * 16u);
       t0[i] = s;
     }
   }
@@ -988,7 +993,6 @@ template <int DH, int MT, int NIO>
 __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const uint16_t *Kc, const uint16_t *Vc, uint16_t *attn_out, int L,
                                             int u0, unsigned &att_seq) {
   constexpr int KT = DH / 32, DT = DH / 16;
-  static_assert(NIO >= 3, "at most three key blocks hold rows of this step: one per wave");
   __amdgpu_buffer_rsrc_t rk = rsrc_of(Kc), rv = rsrc_of(Vc), rqf = rsrc_of(a.qf), ra = rsrc_of(attn_out);
   // per merging wave: DT KB of output tiles, then 512 B of (max, sum) per lane
   constexpr unsigned BUF = DT * 1024u + 512u;
@@ -1072,37 +1076,36 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
         o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[dt]), pb, o[dt], 0, 0, 0);
       }
     };
-    static_assert(LA_MAX_ROWS <= 64, "at most three late key blocks");
     const std::integral_constant<int, 0> plain{};
     const std::integral_constant<int, DEV> coherent{};
-    const int kb_split = L >> 5;
-    const int late = kb_split + (NIO - 1 - v);
-    const bool has_late = late < nkb;
-    const bool any = has_late || v < kb_split;
-    int kb = has_late ? late : v;
-    int ne = has_late ? v : v + NIO;
-    if (has_late) {
-      load_k(coherent, late, true);
-      load_v(coherent, late, true);
-    } else {
-      load_k(plain, v, v < kb_split);
-      load_v(plain, v, v < kb_split);
-    }
-    if (any) {
+    const int kb_split = L >> 5;  // key blocks 0 .. kb_split - 1 end at or before row L ("early")
+    // The blocks that hold rows of this step ("late": at most three, written by other workgroups in
+    // the phase before, so device-scope loads and the mask) are dealt to the waves round-robin and
+    // taken first, one at a time; the early blocks (ordinary loads, every key visible) follow in
+    // the wave's pipeline: the next block's K is requested as soon as the scores are out of the
+    // matrix unit, the next V after P V.
+    for (int kb = kb_split + v; kb < nkb; kb += NIO) {
       float sv[8], corr;
+      load_k(coherent, kb, true);
+      load_v(coherent, kb, true);
       scores(sv);
-      load_k(plain, ne, ne < kb_split);
-      const bf16x8 pb = has_late ? softmax(std::true_type{}, sv, kb, corr) : softmax(std::false_type{}, sv, kb, corr);
+      const bf16x8 pb = softmax(std::true_type{}, sv, kb, corr);
       pv(pb, corr);
-      load_v(plain, ne, ne < kb_split);
-      while (ne < kb_split) {
-        kb = ne;
-        ne += NIO;
+    }
+    if (v < kb_split) {
+      int kb = v, ne = v + NIO;
+      float sv[8], corr;
+      load_k(plain, kb, true);
+      load_v(plain, kb, true);
+      for (;;) {
         scores(sv);
         load_k(plain, ne, ne < kb_split);
-        const bf16x8 pb2 = softmax(std::false_type{}, sv, kb, corr);
-        pv(pb2, corr);
+        const bf16x8 pb = softmax(std::false_type{}, sv, kb, corr);
+        pv(pb, corr);
         load_v(plain, ne, ne < kb_split);
+        if (ne >= kb_split) break;
+        kb = ne;
+        ne += NIO;
       }
     }
     // merge: waves 1 .. NIO-1 leave (o, m, l) in LDS, wave 0 adds them in wave order
@@ -1197,7 +1200,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
   static_assert(NW % NIO == 0, "every IO wave serves the same number of MFMA waves");
   Io io;
   io.lds0 = lds0;
-  io.misc = lds0 + NW * Geo<MT>::REG;
+  io.misc = lds0 + NW * Lay<MT, NW>::REG;
   io.ctl = io.misc + M_CTL;
   io.v = v; io.lane = lane; io.tid = v * 64 + lane;
   io.bar_seq = 0; io.ok = 1;
@@ -1329,12 +1332,12 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *a.err = 1;
     return;
   }
-  if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + NW * Geo<MT>::REG + M_CTL))[threadIdx.x] = 0u;
+  if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + NW * Lay<MT, NW>::REG + M_CTL))[threadIdx.x] = 0u;
   const unsigned lds0 = (unsigned)(uintptr_t)lds;
   // (the schedules are written by threads of the last wave: an IO wave, whose use of scratch memory is harmless)
   if (threadIdx.x >= WG_THREADS - NW)
     build_schedule<NW>(a, Geo<MT>::NTMAX, (int)threadIdx.x - (WG_THREADS - NW),
-                       lds0 + NW * Geo<MT>::REG + M_BYTES + (threadIdx.x - (WG_THREADS - NW)) * TAB_BYTES);
+                       lds0 + NW * Lay<MT, NW>::REG + M_BYTES + (threadIdx.x - (WG_THREADS - NW)) * TAB_BYTES);
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
   if (a.trace && blockIdx.x == 0 && threadIdx.x == 0) a.trace[14] = wall_clock64();  // (timeline: schedules written)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1346,12 +1349,12 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
   } else {
     io_wave_main<MT, NW>(a, lds0, wave - NW, lane, L);
     // a wait that gave up anywhere in the workgroup: tell the host
-    if (lane == 0 && ctl_read(lds0 + NW * Geo<MT>::REG + M_CTL + 4 * K_DEAD) != 0)
+    if (lane == 0 && ctl_read(lds0 + NW * Lay<MT, NW>::REG + M_CTL + 4 * K_DEAD) != 0)
       __hip_atomic_fetch_or(a.err, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (a.trace && lane == 0 && (blockIdx.x == 0 || blockIdx.x == 200)) a.trace[16 + (blockIdx.x ? 8 : 0) + wave] = wall_clock64();  // (timeline: when each wave ends)
     if (a.trace && lane == 0 && blockIdx.x > 2) a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + wave] = wall_clock64();
     if (a.trace && wave == 7 && blockIdx.x == 0) {  // (timeline of MFMA wave 0: LDS -> the workgroup's trace words; the MFMA waves finish before the last epilogue)
-      const unsigned v = ctl_read_lanes(lds0 + NW * Geo<MT>::REG + M_BYTES + NW * TAB_BYTES + 4u * (unsigned)lane);
+      const unsigned v = ctl_read_lanes(lds0 + NW * Lay<MT, NW>::REG + M_BYTES + NW * TAB_BYTES + 4u * (unsigned)lane);
       a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG + lane] = v;  // (the words of workgroups 1 and 2, which leave theirs alone)
     }
   }
