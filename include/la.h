@@ -157,6 +157,21 @@ int la_forward_layers(la_model *m, int layer_begin, int layer_end, float *hidden
 int la_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                       void *stream);
 
+/* la_unembed_argmax for callers that cannot allocate device memory (code under HIP graph
+ * capture, serving loops and harnesses that forbid hipMalloc): same arguments, same kernel
+ * and bit-identical results, but the kernel's scratch memory (barrier words, the f16 operand
+ * of the normalised rows, row statistics, partial arg-max records) is a static device array
+ * of 4.1 MiB that every GPU the library runs on holds until the process ends, instead of
+ * buffers owned by the model.  The call allocates nothing and frees nothing; it launches one
+ * small fill kernel that clears the barrier words, then the unembedding kernel.
+ * Only for LA_BF16 models on the matrix-core path; limits: d_model <= 8192 and
+ * 256 * ceil(vocab / 4096) <= 4096 partial records (vocab <= 65536 on a 256-CU GPU), beyond
+ * which it returns LA_ERANGE; LA_EINVAL for other models.  All calls on one GPU share the
+ * array, whatever the model: calls that overlap in time on one GPU (two streams, two host
+ * threads) race and must be serialised by the caller. */
+int la_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
+                              void *stream);
+
 /* ---- n-gram pool and acceptance (Section 4.3) ----------------------------------------- */
 
 /* Pool keyed by token id: per key at most G distinct (N-1)-token continuations, refreshed

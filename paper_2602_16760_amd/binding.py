@@ -60,6 +60,7 @@ STATE_OFF = {n: getattr(la_step_state, n).offset for n, _ in la_step_state._fiel
 EXPORTS = [
     "la_init_model", "la_model_set_layer", "la_free_model", "la_kv_alloc", "la_kv_set_len", "la_kv_get_len",
     "la_kv_fill", "la_kv_read", "la_free_kv", "la_embed", "la_forward_layers", "la_unembed_argmax",
+    "la_unembed_argmax_noalloc",
     "la_pool_alloc", "la_free_pool", "la_state_init", "la_ngram_accept", "la_lookahead_layout",
     "la_profile_enable", "la_profile_select", "la_profile_read", "la_profile_copy", "la_last_error",
 ]
@@ -85,6 +86,7 @@ def _load():
         "la_embed": (i32, [vp, vp, i32, vp, vp]),
         "la_forward_layers": (i32, [vp, i32, i32, vp, i32, vp, vp, vp, vp]),
         "la_unembed_argmax": (i32, [vp, vp, i32, vp, vp, vp]),
+        "la_unembed_argmax_noalloc": (i32, [vp, vp, i32, vp, vp, vp]),
         "la_pool_alloc": (i32, [i32, i32, i32, C.POINTER(vp)]),
         "la_free_pool": (None, [vp]),
         "la_state_init": (i32, [vp, vp, C.POINTER(la_lookahead_desc), vp, i32, i32, i32, vp, vp]),
@@ -204,6 +206,11 @@ def la_forward_layers(model, layer_begin, layer_end, hidden, pos, vis, kv, strea
 def la_unembed_argmax(model, hidden, ids, top2=None, stream=None):
     assert ids.dtype == torch.int32
     _check(lib.la_unembed_argmax(model, _ptr(hidden), hidden.shape[0], _ptr(ids), _ptr(top2), _stream(stream)))
+
+
+def la_unembed_argmax_noalloc(model, hidden, ids, top2=None, stream=None):
+    assert ids.dtype == torch.int32
+    _check(lib.la_unembed_argmax_noalloc(model, _ptr(hidden), hidden.shape[0], _ptr(ids), _ptr(top2), _stream(stream)))
 
 
 def la_pool_alloc(vocab, N, G):

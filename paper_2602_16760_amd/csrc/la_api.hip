@@ -404,3 +404,11 @@ extern "C" int la_unembed_argmax(la_model *m, const float *hidden, int Bp, int32
   if (m->use_mfma) return mfma_unembed_argmax(m, hidden, Bp, ids, top2, s);
   return generic_unembed_argmax(m, hidden, Bp, ids, top2, s);
 }
+
+extern "C" int la_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2, void *stream) {
+  LA_REQUIRE(m && hidden && ids, LA_EINVAL, "NULL argument");
+  LA_REQUIRE(Bp >= 1 && Bp <= LA_MAX_ROWS, LA_EINVAL, "Bp=%d outside [1, %d]", Bp, LA_MAX_ROWS);
+  LA_REQUIRE(m->use_mfma, LA_EINVAL, "only models on the matrix-core path (LA_BF16, supported shape) have this entry point");
+  LA_REQUIRE(m->g_final, LA_EINVAL, "model was created without final norm / unembedding");
+  return mfma_unembed_argmax_noalloc(m, hidden, Bp, ids, top2, (hipStream_t)stream);
+}

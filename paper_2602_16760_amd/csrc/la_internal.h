@@ -106,4 +106,6 @@ int mfma_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32
                  const uint64_t *vis, la_kv *kv, hipStream_t s);
 int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                         hipStream_t s);
+int mfma_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
+                                hipStream_t s);
 }  // namespace la

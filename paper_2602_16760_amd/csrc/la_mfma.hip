@@ -3,6 +3,7 @@
 #include <stdio.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 #include "la_rstack.h"
@@ -191,11 +192,17 @@ void mfma_destroy(la_model *m) {
   m->mf = nullptr;
 }
 
+static int na_setup(int device);  // address of the static scratch array on this device (defined with its entry point below)
+
 int mfma_create(la_model *m) {
   const la_model_desc &d = m->d;
   MfmaModel *f = new (std::nothrow) MfmaModel();
   LA_REQUIRE(f != nullptr, LA_ENOMEM, "out of host memory");
   m->mf = f;
+  {
+    int rc = na_setup(m->device);
+    if (rc) return rc;
+  }
   hipDeviceProp_t prop;
   LA_HIP(hipGetDeviceProperties(&prop, m->device));
   int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
@@ -321,15 +328,21 @@ int mfma_set_head(la_model *m, const void *unembed, hipStream_t s) {
 
 static GemmDev dev_plan(const GemmPlan &p) { return GemmDev{p.KT, p.ntiles, p.ntp}; }
 
-static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barriers, hipStream_t s) {
-  if (f->epoch > (1u << 26)) {  // keep the monotonic counters far from wrapping
-    zero_u32_kernel<<<ceil_div(SYNC_STRIDE * 66, 256), 256, 0, s>>>(f->sync, SYNC_STRIDE * 66);
-    f->epoch = 0;
+// fresh_sync: a.sync was cleared on `s` just before and does not belong to the model, so the launch starts at barrier
+// epoch 0 and leaves the model's epoch alone; such launches are not traced.
+static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barriers, hipStream_t s, bool fresh_sync = false) {
+  if (fresh_sync) {
+    a.epoch0 = 0;
+  } else {
+    if (f->epoch > (1u << 26)) {  // keep the monotonic counters far from wrapping
+      zero_u32_kernel<<<ceil_div(SYNC_STRIDE * 66, 256), 256, 0, s>>>(f->sync, SYNC_STRIDE * 66);
+      f->epoch = 0;
+    }
+    a.epoch0 = f->epoch;
+    f->epoch += (unsigned)n_barriers;
   }
-  a.epoch0 = f->epoch;
-  f->epoch += (unsigned)n_barriers;
   a.n_groups = (unsigned)ceil_div(f->n_wgs, SYNC_GROUP);
-  a.trace = f->trace;
+  a.trace = fresh_sync ? nullptr : f->trace;
   a.trace_phases = f->trace_phases;
   a.trace_sel = env_int("LA_TRACE_SEL", 6);
   a.trace_seg = env_int("LA_TRACE_SEG", 2);
@@ -353,7 +366,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     }
   }
   if (rc) return rc;
-  if (f->trace) {  // debugging aid: timeline of workgroup 0 (100 MHz clock) and producer statistics
+  if (a.trace) {  // debugging aid: timeline of workgroup 0 (100 MHz clock) and producer statistics
     int np = n_barriers + 1;
     std::vector<unsigned long long> h((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs);
     LA_HIP(hipStreamSynchronize(s));
@@ -576,6 +589,70 @@ int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, 
   a.max_len = LA_MAX_ROWS;
   a.err = f->zero_len + 1;
   return launch_stack("unembed_argmax", f, a, 2, s);
+}
+
+// ---- the unembedding for callers that cannot allocate ------------------------------------------------
+// Everything the unembedding kernel needs beyond the caller's buffers and the packed weights sits in one static array per
+// GPU: the barrier words and the {cache length 0, error word} pair (cleared by every call), the f16 operand fragments of
+// the normalised rows, the row statistics and the partial arg-max records (each fully rewritten, for the rows in use,
+// before it is read).  Calls that overlap on one GPU would share these words and race.
+constexpr size_t NA_SYNC_BYTES = (size_t)SYNC_STRIDE * 66 * 4;
+constexpr size_t NA_ZERO_BYTES = NA_SYNC_BYTES + 256;  // barrier words, then the length / error pair
+constexpr int NA_MAX_D = 8192;                         // d_model
+constexpr int NA_MAX_PARTS = 4096;                     // workgroups x partial records per workgroup
+constexpr size_t NA_OFF_XA = NA_ZERO_BYTES;
+constexpr size_t NA_OFF_RSQ = NA_OFF_XA + (size_t)LA_MAX_ROWS * NA_MAX_D * 2;
+constexpr size_t NA_OFF_TOP = NA_OFF_RSQ + (size_t)LA_MAX_ROWS * (NA_MAX_D / 16) * 4;
+constexpr size_t NA_BYTES = NA_OFF_TOP + (size_t)NA_MAX_PARTS * 64 * sizeof(Top);  // 4.1 MiB
+static_assert(NA_OFF_XA % 256 == 0 && NA_OFF_RSQ % 256 == 0 && NA_OFF_TOP % 256 == 0, "256-byte aligned parts");
+static __device__ __align__(256) unsigned char scratch[NA_BYTES];
+
+constexpr int NA_MAX_DEVICES = 64;
+static unsigned char *na_ptr[NA_MAX_DEVICES] = {};  // this GPU's copy of `scratch`, looked up once per device
+static std::mutex na_mutex;
+
+// Called at model creation with the model's device current.
+static int na_setup(int device) {
+  if (device < 0 || device >= NA_MAX_DEVICES) return LA_OK;  // the entry point reports the missing address
+  std::lock_guard<std::mutex> lock(na_mutex);
+  if (na_ptr[device]) return LA_OK;
+  unsigned char *p = nullptr;
+  LA_HIP(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+  LA_REQUIRE(p != nullptr, LA_EHIP, "no device address for the static scratch array");
+  LA_HIP(hipMemset(p, 0, NA_BYTES));
+  na_ptr[device] = p;
+  return LA_OK;
+}
+
+int mfma_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2, hipStream_t s) {
+  MfmaModel *f = m->mf;
+  LA_REQUIRE(f->ustream != nullptr, LA_EINVAL, "model was created without an unembedding matrix");
+  LA_REQUIRE(m->d.d_model <= NA_MAX_D, LA_ERANGE, "d_model=%d exceeds the %d the static scratch array holds", m->d.d_model, NA_MAX_D);
+  LA_REQUIRE((long long)f->n_wgs * f->un_parts_per_cu <= NA_MAX_PARTS, LA_ERANGE,
+             "vocab=%d needs %lld partial arg-max records, the static scratch array holds %d", m->d.vocab,
+             (long long)f->n_wgs * f->un_parts_per_cu, NA_MAX_PARTS);
+  unsigned char *base = (m->device >= 0 && m->device < NA_MAX_DEVICES) ? na_ptr[m->device] : nullptr;
+  LA_REQUIRE(base != nullptr, LA_EHIP, "the static scratch array has no address on device %d", m->device);
+  zero_u32_kernel<<<ceil_div((int)(NA_ZERO_BYTES / 4), 256), 256, 0, s>>>((unsigned *)base, (int)(NA_ZERO_BYTES / 4));
+  LA_HIP(hipGetLastError());
+  StackArgs a = base_stack_args(m, Bp);
+  a.mode = 1;
+  a.wstream = f->ustream;
+  a.cu_bytes = f->ucu_bytes;
+  a.seg_frags = (unsigned)(f->ucu_bytes / 1024);
+  a.sync = (unsigned *)base;
+  a.xa = (uint16_t *)(base + NA_OFF_XA);
+  a.rsq = (float *)(base + NA_OFF_RSQ);
+  a.x = const_cast<float *>(hidden);
+  a.g_final = m->g_final;
+  a.un_part = (Top *)(base + NA_OFF_TOP);
+  a.un_parts_per_cu = f->un_parts_per_cu;
+  a.ids = ids;
+  a.top2 = top2;
+  a.L_dev = (int32_t *)(base + NA_SYNC_BYTES);
+  a.max_len = LA_MAX_ROWS;
+  a.err = (int32_t *)(base + NA_SYNC_BYTES) + 1;
+  return launch_stack("unembed_argmax", f, a, 2, s, true);
 }
 
 }  // namespace la
