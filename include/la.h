@@ -29,6 +29,22 @@
  *    2^-14 or more converts without loss, smaller ones to within 2^-25) with activations
  *    rounded to half precision (values beyond +-65504 saturate); attention multiplies in
  *    bfloat16.
+ *  - Errors raised on the device.  Two conditions are only known to a kernel: a block that
+ *    does not fit the cache at the device-side length (the launch is then skipped as a
+ *    whole), and a grid barrier of the persistent kernel that gave up waiting (its results
+ *    are invalid).  The kernel records the code in the model's device error word and in a
+ *    word of pinned host memory.  Every later call that takes the model or one of its
+ *    caches looks at the host word first, without synchronising, and if it is set returns
+ *    LA_ERANGE / LA_EHIP once instead of doing its work; la_kv_get_len, which synchronises,
+ *    reports it for certain.  la_ngram_accept copies the device word into
+ *    la_step_state.error.  After the report the next launch clears the word and the barrier
+ *    state, so the model stays usable.
+ *  - One stream at a time.  A la_model carries scratch memory (operand buffers, barrier
+ *    words, RoPE table) that every launch on it uses: a model, and the caches made for it,
+ *    may be in use on one stream at a time; two models are independent.  The persistent
+ *    kernel of the matrix-core path waits at grid barriers for all of its workgroups, so
+ *    it needs the GPU's compute units free of other long-running kernels while it runs.
+ *    Free every la_kv before the la_model it was made for.
  *  - A block has Bp <= LA_MAX_ROWS rows.  Row b sits at cache row L+b while the block is
  *    in flight, where L is the committed cache length kept on the device inside la_kv.
  */
@@ -49,7 +65,7 @@ typedef enum {
   LA_EINVAL = -1, /* bad shape, NULL pointer, Bp out of range, unsupported combination */
   LA_ENOMEM = -2, /* device or host allocation failed */
   LA_ERANGE = -3, /* the block would not fit: L + Bp > max_len, or layer out of range */
-  LA_EHIP = -4    /* a HIP call failed; la_last_error() has its text */
+  LA_EHIP = -4    /* a HIP call failed, or a grid barrier gave up; la_last_error() has its text */
 } la_status;
 
 typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
@@ -109,9 +125,16 @@ typedef struct {
  * of device pointers, or NULL to add layers later with la_model_set_layer.  embed [V, d],
  * unembed [d, V] (model dtype) and g_final [d] (float) are device pointers; each may be
  * NULL if la_embed / la_unembed_argmax will not be called.
- * LA_EINVAL: a dimension is not positive, Hq is not a multiple of Hkv, head_dim is odd,
- * or (LA_BF16) d_model, Hq*dh, d_ffn are not multiples of 32, head_dim is not 64 or 128,
- * or vocab is not a multiple of 16. */
+ * LA_EINVAL: a dimension is not positive, Hq is not a multiple of Hkv, head_dim is odd or
+ * above 256, or the GPU cannot keep the persistent kernel's workgroups (one per compute unit)
+ * resident at once.
+ * Two kernel paths exist.  LA_BF16 models run on the matrix-core path when d_model is a
+ * multiple of 64 and at most 8192, Hq*dh and d_ffn are multiples of 32, (Hq + 2 Hkv)*dh and
+ * vocab are multiples of 16, head_dim is 64 or 128 and Hq / Hkv <= 8.  Every other model
+ * (LA_F32, or LA_BF16 of another shape) runs on plain kernels with float arithmetic and the
+ * same results within the stated tolerance, far slower: they are the correctness path, not a
+ * performance path.  The first la_forward_layers after weights were set synchronises
+ * `stream` once (the table of norm-gain pointers is uploaded from pageable host memory). */
 int la_init_model(const la_model_desc *desc, const la_layer_weights *layers, const void *embed,
                   const float *g_final, const void *unembed, void *stream, la_model **out);
 int la_model_set_layer(la_model *m, int layer, const la_layer_weights *w, void *stream);
@@ -121,7 +144,9 @@ void la_free_model(la_model *m);
 
 /* Cache for all layers of `m`: per layer K and V of max_len rows [Hkv, dh] in the model
  * dtype, keys stored after RoPE.  max_len must leave room for the in-flight block:
- * la_forward_layers needs L + Bp <= max_len.  The committed length L starts at 0. */
+ * la_forward_layers needs L + Bp <= max_len.  The committed length L starts at 0.
+ * LA_EINVAL on the matrix-core path if one layer's K rows would reach 2 GiB
+ * (max_len * Hkv * dh * 2 bytes: about 1M rows at Hkv*dh = 1024). */
 int la_kv_alloc(const la_model *m, int max_len, la_kv **out);
 /* Sets L (the paper's cache crop: rows >= L are dead). */
 int la_kv_set_len(la_kv *kv, int L, void *stream);
@@ -202,6 +227,17 @@ int la_ngram_accept(la_pool *p, la_kv *kv, const la_lookahead_desc *la, const in
  * vis_host [Bp] are host arrays. */
 int la_lookahead_layout(const la_lookahead_desc *la, int t, int n_cand, int Bp, int32_t *pos_host,
                         uint64_t *vis_host);
+
+/* Host helper: positions t, t+1, ... and causal masks (row i sees block rows 0..i) of a block
+ * of n consecutive tokens, as a prompt chunk is run (Section 4.1 step 1: the prompt goes
+ * through the same layers before generation).  pos_host [n], vis_host [n] are host arrays;
+ * 1 <= n <= LA_MAX_ROWS. */
+int la_causal_layout(int t, int n, int32_t *pos_host, uint64_t *vis_host);
+
+/* Sets how many times a workgroup polls a grid barrier's release word (about a microsecond
+ * per poll) before it gives up and the launch reports LA_EHIP; 0 restores the default
+ * (2^21, about two seconds).  Takes effect from the next launch on the model. */
+int la_set_barrier_timeout(la_model *m, unsigned polls);
 
 /* ---- diagnostics ---------------------------------------------------------------------- */
 

@@ -60,7 +60,7 @@ STATE_OFF = {n: getattr(la_step_state, n).offset for n, _ in la_step_state._fiel
 EXPORTS = [
     "la_init_model", "la_model_set_layer", "la_free_model", "la_kv_alloc", "la_kv_set_len", "la_kv_get_len",
     "la_kv_fill", "la_kv_read", "la_free_kv", "la_embed", "la_forward_layers", "la_unembed_argmax",
-    "la_unembed_argmax_noalloc",
+    "la_unembed_argmax_noalloc", "la_causal_layout", "la_set_barrier_timeout",
     "la_pool_alloc", "la_free_pool", "la_state_init", "la_ngram_accept", "la_lookahead_layout",
     "la_profile_enable", "la_profile_select", "la_profile_read", "la_profile_copy", "la_last_error",
 ]
@@ -92,6 +92,8 @@ def _load():
         "la_state_init": (i32, [vp, vp, C.POINTER(la_lookahead_desc), vp, i32, i32, i32, vp, vp]),
         "la_ngram_accept": (i32, [vp, vp, C.POINTER(la_lookahead_desc), vp, vp, vp, i32, vp]),
         "la_lookahead_layout": (i32, [C.POINTER(la_lookahead_desc), i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
+        "la_causal_layout": (i32, [i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
+        "la_set_barrier_timeout": (i32, [vp, C.c_uint]),
         "la_profile_enable": (i32, [i32]),
         "la_profile_select": (i32, [C.c_char_p]),
         "la_profile_read": (i32, [C.POINTER(la_profile_entry), i32]),
@@ -241,6 +243,18 @@ def la_lookahead_layout(W, N, G, t, n_cand, Bp):
     vis = (C.c_uint64 * Bp)()
     _check(lib.la_lookahead_layout(C.byref(d), t, n_cand, Bp, pos, vis))
     return np.array(pos, dtype=np.int32), np.array(vis, dtype=np.uint64)
+
+
+def la_causal_layout(t, n):
+    """Host helper -> (pos int32[n], vis uint64[n]) numpy arrays of a causal block of n tokens at position t."""
+    pos = (C.c_int32 * n)()
+    vis = (C.c_uint64 * n)()
+    _check(lib.la_causal_layout(t, n, pos, vis))
+    return np.array(pos, dtype=np.int32), np.array(vis, dtype=np.uint64)
+
+
+def la_set_barrier_timeout(model, polls):
+    _check(lib.la_set_barrier_timeout(model, polls))
 
 
 def la_profile_enable(on: bool):

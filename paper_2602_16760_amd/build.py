@@ -41,7 +41,15 @@ def _stale(target: str, deps) -> bool:
 
 
 def build(force: bool = False, verbose: bool = True) -> str:
+    """Compiles every source and links liblookahead.so.  LA_EXPERIMENTS=1 in the environment builds
+    the variant with device timelines (LA_TRACE) and timing experiments (LA_DBG) compiled in."""
     os.makedirs(OBJ, exist_ok=True)
+    flags = FLAGS + (["-DLA_EXPERIMENTS"] if os.environ.get("LA_EXPERIMENTS") == "1" else [])
+    stamp = os.path.join(OBJ, "flags.txt")
+    if not os.path.exists(stamp) or open(stamp).read() != " ".join(flags):
+        force = True  # objects of another variant
+        with open(stamp, "w") as fh:
+            fh.write(" ".join(flags))
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     headers.append(os.path.join(ROOT, "include", "la.h"))
     hipcc = _hipcc()
@@ -52,7 +60,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
         o = os.path.join(OBJ, src.replace(".hip", ".o"))
         objs.append(o)
         if force or _stale(o, [s] + headers):
-            jobs.append([hipcc, "-x", "hip", "-c", s, "-o", o] + FLAGS)
+            jobs.append([hipcc, "-x", "hip", "-c", s, "-o", o] + flags)
 
     def run(cmd):
         if verbose:

@@ -139,8 +139,9 @@ __global__ void state_init_kernel(PoolView p, la_step_state *st, const int32_t *
 }
 
 __global__ void accept_kernel(PoolView p, la_step_state *st, const int32_t *ids, int32_t *emitted, int max_total,
-                              int W, int N, int G, int32_t *kv_L) {
+                              int W, int N, int G, int32_t *kv_L, const int32_t *err) {
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->error = *err;  // what the launches before this one on the model raised (0: nothing)
   int remaining = max_total - st->n_emitted;
   if (remaining <= 0) {  // budget spent: the step is a no-op
     st->last_emitted = 0;
@@ -276,6 +277,7 @@ static PoolView view(la_pool *p) { return PoolView{p->stamp, p->toks, p->counter
 extern "C" int la_state_init(la_pool *p, la_kv *kv, const la_lookahead_desc *d, const int32_t *prompt, int P, int Bp,
                              int seed_pool, la_step_state *state, void *stream) {
   LA_REQUIRE(p && kv && prompt && state, LA_EINVAL, "NULL argument");
+  LA_PENDING(kv->m);
   int rc = check_la(d, Bp);
   if (rc) return rc;
   LA_REQUIRE(P >= 1, LA_EINVAL, "prompt must have at least one token");
@@ -299,6 +301,7 @@ extern "C" int la_state_init(la_pool *p, la_kv *kv, const la_lookahead_desc *d, 
 extern "C" int la_ngram_accept(la_pool *p, la_kv *kv, const la_lookahead_desc *d, const int32_t *ids,
                                la_step_state *state, int32_t *emitted, int max_total, void *stream) {
   LA_REQUIRE(p && kv && ids && state && emitted, LA_EINVAL, "NULL argument");
+  LA_PENDING(kv->m);
   int rc = check_la(d, 1 + (d ? (d->W + d->G) * (d->N - 1) : 0));
   if (rc) return rc;
   LA_REQUIRE(p->N == d->N && p->G == d->G, LA_EINVAL, "pool was allocated for N=%d G=%d", p->N, p->G);
@@ -306,7 +309,7 @@ extern "C" int la_ngram_accept(la_pool *p, la_kv *kv, const la_lookahead_desc *d
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps("ngram_accept", s);
-    accept_kernel<<<1, 64, 0, s>>>(view(p), state, ids, emitted, max_total, d->W, d->N, d->G, kv->L_dev);
+    accept_kernel<<<1, 64, 0, s>>>(view(p), state, ids, emitted, max_total, d->W, d->N, d->G, kv->L_dev, kv->err_dev);
   }
   if (d->N >= 2) {
     ProfScope ps("kv_commit", s);

@@ -139,6 +139,33 @@ extern "C" int la_profile_copy(void *dst, const void *src, size_t bytes, void *s
   return LA_OK;
 }
 
+namespace la {
+int pending_error(const la_model *m) {
+  if (!m || !m->err_host) return LA_OK;
+  volatile int32_t *w = m->err_host;
+  int32_t v = *w;
+  if (v == 0) return LA_OK;
+  *w = 0;
+  const_cast<la_model *>(m)->recover = true;
+  if (v & 4) {
+    set_error("an earlier launch on this model gave up waiting at a grid barrier (every workgroup of the persistent kernel "
+              "must be resident at once); its results are invalid");
+    return LA_EHIP;
+  }
+  set_error("an earlier block did not fit the cache (L + Bp > max_len) and was skipped");
+  return LA_ERANGE;
+}
+
+int recover_if_needed(la_model *m, hipStream_t s) {
+  if (!m->recover) return LA_OK;
+  set_i32_kernel<<<1, 1, 0, s>>>(m->err_dev, 0);
+  LA_HIP(hipGetLastError());
+  if (m->mf) mfma_reset_sync(m, s);
+  m->recover = false;
+  return LA_OK;
+}
+}  // namespace la
+
 static void *dev_alloc(size_t bytes) {
   void *p = nullptr;
   if (hipMalloc(&p, bytes ? bytes : 1) != hipSuccess) return nullptr;
@@ -153,9 +180,10 @@ extern "C" void la_free_model(la_model *m) {
     for (void *p : ps)
       if (p) (void)hipFree(p);
   }
-  void *ps[] = {m->embed, m->unembed, m->g_final, m->h, m->qkv, m->attn, m->gu, m->act, m->logits, m->rope_cs};
+  void *ps[] = {m->embed, m->unembed, m->g_final, m->h, m->qkv, m->attn, m->gu, m->act, m->logits, m->rope_cs, m->err_dev};
   for (void *p : ps)
     if (p) (void)hipFree(p);
+  if (m->err_host) (void)hipHostFree(m->err_host);
   delete m;
 }
 
@@ -185,6 +213,12 @@ extern "C" int la_init_model(const la_model_desc *desc, const la_layer_weights *
   size_t R = LA_MAX_ROWS;
   bool ok = true;
   ok = ok && (m->rope_cs = (float *)dev_alloc(R * d.head_dim * sizeof(float)));
+  ok = ok && (m->err_dev = (int32_t *)dev_alloc(4)) && hipMemset(m->err_dev, 0, 4) == hipSuccess;
+  ok = ok && hipHostMalloc((void **)&m->err_host, 64, hipHostMallocMapped) == hipSuccess;
+  if (ok) {
+    memset(m->err_host, 0, 64);
+    ok = hipHostGetDevicePointer((void **)&m->err_map, m->err_host, 0) == hipSuccess;
+  }
   if (!m->use_mfma) {
     ok = ok && (m->h = (float *)dev_alloc(R * d.d_model * 4));
     ok = ok && (m->qkv = (float *)dev_alloc(R * m->nqkv() * 4));
@@ -231,6 +265,7 @@ extern "C" int la_init_model(const la_model_desc *desc, const la_layer_weights *
 
 extern "C" int la_model_set_layer(la_model *m, int layer, const la_layer_weights *w, void *stream) {
   LA_REQUIRE(m && w, LA_EINVAL, "NULL argument");
+  LA_PENDING(m);
   LA_REQUIRE(layer >= 0 && layer < m->d.n_layers, LA_ERANGE, "layer %d outside [0, %d)", layer, m->d.n_layers);
   LA_REQUIRE(w->wq && w->wk && w->wv && w->wo && w->wgate && w->wup && w->wdown && w->g_attn && w->g_mlp, LA_EINVAL,
              "layer %d: NULL weight pointer", layer);
@@ -273,7 +308,7 @@ extern "C" int la_model_set_layer(la_model *m, int layer, const la_layer_weights
 // ---- KV cache -----------------------------------------------------------------------------
 extern "C" void la_free_kv(la_kv *kv) {
   if (!kv) return;
-  void *ps[] = {kv->K, kv->V, kv->L_dev, kv->err_dev};
+  void *ps[] = {kv->K, kv->V, kv->L_dev};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   delete kv;
@@ -283,6 +318,10 @@ extern "C" int la_kv_alloc(const la_model *m, int max_len, la_kv **out) {
   LA_REQUIRE(out != nullptr, LA_EINVAL, "out is NULL");
   *out = nullptr;
   LA_REQUIRE(m != nullptr && max_len > 0, LA_EINVAL, "bad arguments to la_kv_alloc");
+  // the matrix-core path addresses a layer's K (and V) through 32-bit byte offsets
+  LA_REQUIRE(!m->use_mfma || ((size_t)max_len + 31) / 32 * 32 * m->d.n_kv_heads * m->d.head_dim * 2 < ((size_t)1 << 31), LA_EINVAL,
+             "max_len=%d: one layer's K rows would reach 2 GiB (limit %zu rows for this model)", max_len,
+             (((size_t)1 << 31) / ((size_t)m->d.n_kv_heads * m->d.head_dim * 2) - 1) / 32 * 32);
   la_kv *kv = new (std::nothrow) la_kv();
   LA_REQUIRE(kv != nullptr, LA_ENOMEM, "out of host memory");
   kv->m = m;
@@ -294,15 +333,15 @@ extern "C" int la_kv_alloc(const la_model *m, int max_len, la_kv **out) {
   kv->K = dev_alloc(bytes);
   kv->V = dev_alloc(bytes);
   kv->L_dev = (int32_t *)dev_alloc(4);
-  kv->err_dev = (int32_t *)dev_alloc(4);
-  if (!kv->K || !kv->V || !kv->L_dev || !kv->err_dev) {
+  kv->err_dev = m->err_dev;
+  if (!kv->K || !kv->V || !kv->L_dev) {
     la_free_kv(kv);
     set_error("KV cache allocation of 2 x %zu bytes failed", bytes);
     return LA_ENOMEM;
   }
   // zero everything once: rows of the key-blocked V layout are read in blocks of 32
   if (hipMemset(kv->K, 0, bytes) != hipSuccess || hipMemset(kv->V, 0, bytes) != hipSuccess ||
-      hipMemset(kv->L_dev, 0, 4) != hipSuccess || hipMemset(kv->err_dev, 0, 4) != hipSuccess) {
+      hipMemset(kv->L_dev, 0, 4) != hipSuccess) {
     la_free_kv(kv);
     set_error("KV cache clear failed");
     return LA_EHIP;
@@ -313,6 +352,7 @@ extern "C" int la_kv_alloc(const la_model *m, int max_len, la_kv **out) {
 
 extern "C" int la_kv_set_len(la_kv *kv, int L, void *stream) {
   LA_REQUIRE(kv != nullptr, LA_EINVAL, "kv is NULL");
+  LA_PENDING(kv->m);
   LA_REQUIRE(L >= 0 && L <= kv->max_len, LA_ERANGE, "L=%d outside [0, %d]", L, kv->max_len);
   set_i32_kernel<<<1, 1, 0, (hipStream_t)stream>>>(kv->L_dev, L);
   LA_HIP(hipGetLastError());
@@ -328,13 +368,20 @@ extern "C" int la_kv_get_len(la_kv *kv, int *L_host, void *stream) {
   LA_HIP(hipStreamSynchronize((hipStream_t)stream));
   *L_host = v[0];
   kv->L_bound = v[0];
+  if (v[1] != 0) {  // the stream has drained: the device word is final; report it once and start clean
+    la_model *mm = const_cast<la_model *>(kv->m);
+    *(volatile int32_t *)mm->err_host = 0;
+    mm->recover = true;
+  }
   LA_REQUIRE((v[1] & 4) == 0, LA_EHIP, "a grid barrier timed out: the persistent kernel needs every workgroup resident at once");
   LA_REQUIRE(v[1] == 0, LA_ERANGE, "a block did not fit the cache (L + Bp > max_len) and was skipped");
+  LA_PENDING(kv->m);
   return LA_OK;
 }
 
 static int kv_copy(la_kv *kv, int layer, int row0, void *k, void *v, int n, int to_cache, hipStream_t s) {
   LA_REQUIRE(kv != nullptr, LA_EINVAL, "kv is NULL");
+  LA_PENDING(kv->m);
   if (n == 0) return LA_OK;
   LA_REQUIRE(k && v, LA_EINVAL, "NULL argument");
   LA_REQUIRE(layer >= 0 && layer < kv->n_layers, LA_ERANGE, "layer %d outside [0, %d)", layer, kv->n_layers);
@@ -364,6 +411,7 @@ extern "C" int la_kv_read(la_kv *kv, int layer, int row0, int n, void *k, void *
 // ---- the step -----------------------------------------------------------------------------
 extern "C" int la_embed(la_model *m, const int32_t *tok, int Bp, float *hidden, void *stream) {
   LA_REQUIRE(m && tok && hidden, LA_EINVAL, "NULL argument");
+  LA_PENDING(m);
   LA_REQUIRE(Bp >= 1 && Bp <= LA_MAX_ROWS, LA_EINVAL, "Bp=%d outside [1, %d]", Bp, LA_MAX_ROWS);
   LA_REQUIRE(m->embed != nullptr, LA_EINVAL, "model was created without an embedding table");
   hipStream_t s = (hipStream_t)stream;
@@ -380,6 +428,7 @@ extern "C" int la_forward_layers(la_model *m, int layer_begin, int layer_end, fl
                                  const int32_t *pos, const uint64_t *vis, la_kv *kv, void *stream) {
   LA_REQUIRE(m && hidden && pos && vis && kv, LA_EINVAL, "NULL argument");
   LA_REQUIRE(kv->m == m, LA_EINVAL, "the cache belongs to another model");
+  LA_PENDING(m);
   LA_REQUIRE(Bp >= 1 && Bp <= LA_MAX_ROWS, LA_EINVAL, "Bp=%d outside [1, %d]", Bp, LA_MAX_ROWS);
   LA_REQUIRE(layer_begin >= 0 && layer_begin <= layer_end && layer_end <= m->d.n_layers, LA_ERANGE,
              "layers [%d, %d) outside the model's %d layers", layer_begin, layer_end, m->d.n_layers);
@@ -392,6 +441,10 @@ extern "C" int la_forward_layers(la_model *m, int layer_begin, int layer_end, fl
   }
   for (int l = layer_begin; l < layer_end; ++l)
     LA_REQUIRE(m->layers[l].set, LA_EINVAL, "layer %d has no weights", l);
+  {
+    int rc = recover_if_needed(m, s);
+    if (rc) return rc;
+  }
   if (m->use_mfma) return mfma_forward(m, layer_begin, layer_end, hidden, Bp, pos, vis, kv, s);
   return generic_forward(m, layer_begin, layer_end, hidden, Bp, pos, vis, kv, s);
 }
@@ -400,7 +453,12 @@ extern "C" int la_unembed_argmax(la_model *m, const float *hidden, int Bp, int32
   LA_REQUIRE(m && hidden && ids, LA_EINVAL, "NULL argument");
   LA_REQUIRE(Bp >= 1 && Bp <= LA_MAX_ROWS, LA_EINVAL, "Bp=%d outside [1, %d]", Bp, LA_MAX_ROWS);
   LA_REQUIRE(m->g_final && (m->unembed || m->use_mfma), LA_EINVAL, "model was created without final norm / unembedding");
+  LA_PENDING(m);
   hipStream_t s = (hipStream_t)stream;
+  {
+    int rc = recover_if_needed(m, s);
+    if (rc) return rc;
+  }
   if (m->use_mfma) return mfma_unembed_argmax(m, hidden, Bp, ids, top2, s);
   return generic_unembed_argmax(m, hidden, Bp, ids, top2, s);
 }
@@ -410,5 +468,26 @@ extern "C" int la_unembed_argmax_noalloc(la_model *m, const float *hidden, int B
   LA_REQUIRE(Bp >= 1 && Bp <= LA_MAX_ROWS, LA_EINVAL, "Bp=%d outside [1, %d]", Bp, LA_MAX_ROWS);
   LA_REQUIRE(m->use_mfma, LA_EINVAL, "only models on the matrix-core path (LA_BF16, supported shape) have this entry point");
   LA_REQUIRE(m->g_final, LA_EINVAL, "model was created without final norm / unembedding");
+  LA_PENDING(m);
+  {
+    int rc = recover_if_needed(m, (hipStream_t)stream);
+    if (rc) return rc;
+  }
   return mfma_unembed_argmax_noalloc(m, hidden, Bp, ids, top2, (hipStream_t)stream);
+}
+
+extern "C" int la_set_barrier_timeout(la_model *m, unsigned polls) {
+  LA_REQUIRE(m != nullptr, LA_EINVAL, "NULL argument");
+  m->barrier_spins = polls;
+  return LA_OK;
+}
+
+extern "C" int la_causal_layout(int t, int n, int32_t *pos_host, uint64_t *vis_host) {
+  LA_REQUIRE(pos_host && vis_host, LA_EINVAL, "NULL output");
+  LA_REQUIRE(n >= 1 && n <= LA_MAX_ROWS && t >= 0, LA_EINVAL, "n=%d outside [1, %d] or t=%d negative", n, LA_MAX_ROWS, t);
+  for (int i = 0; i < n; ++i) {
+    pos_host[i] = t + i;
+    vis_host[i] = i == 63 ? ~0ull : ((1ull << (i + 1)) - 1ull);
+  }
+  return LA_OK;
 }

@@ -93,11 +93,14 @@ __global__ void gemm_generic_kernel(const float *A, int lda, const T *W, int ldw
 // Rotates q (in place) and k by the row's position and writes k, v to cache rows L+b.
 template <typename T>
 __global__ void rope_kvwrite_kernel(float *qkv, int Hq, int Hkv, int dh, const float *cs, T *Kc, T *Vc,
-                                    const int32_t *L_dev, int max_len, int Bp, int32_t *err) {
+                                    const int32_t *L_dev, int max_len, int Bp, int32_t *err, int32_t *err_map) {
   int b = blockIdx.x;
   int L = *L_dev;
   if (L < 0 || L + Bp > max_len) {
-    if (threadIdx.x == 0) *err = 1;
+    if (threadIdx.x == 0) {  // the device word, and the host's mapped word (read without synchronising)
+      *err = 1;
+      __hip_atomic_store(err_map, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     return;
   }
   int half = dh / 2;
@@ -266,7 +269,7 @@ static int forward_t(la_model *m, int lb, int le, float *hidden, int Bp, const i
     {
       ProfScope p("rope_kvwrite", s);
       rope_kvwrite_kernel<T><<<Bp, 256, 0, s>>>(m->qkv, d.n_q_heads, d.n_kv_heads, d.head_dim, m->rope_cs, Kc, Vc,
-                                                 kv->L_dev, kv->max_len, Bp, kv->err_dev);
+                                                 kv->L_dev, kv->max_len, Bp, kv->err_dev, m->err_map);
     }
     {
       ProfScope p("attention", s);

@@ -62,6 +62,14 @@ struct la_model {
   float *h = nullptr, *qkv = nullptr, *attn = nullptr, *gu = nullptr, *act = nullptr, *logits = nullptr;
   float *rope_cs = nullptr;  // [LA_MAX_ROWS][dh/2][2] cos, sin at each row's position
   la::MfmaModel *mf = nullptr;
+  // Errors raised by kernels (a block that does not fit the cache: 1; a grid barrier that gave up: 4).  err_dev is the
+  // device word the kernels OR into (the caches of this model alias it); err_host is one word of mapped pinned host
+  // memory (device alias err_map) that a kernel stores its code to when it raises one, so that the next entry point
+  // on this model or one of its caches can report the error without synchronising.
+  int32_t *err_dev = nullptr;
+  int32_t *err_host = nullptr, *err_map = nullptr;
+  bool recover = false;          // an error was reported: the next launch clears err_dev and the barrier words first
+  unsigned barrier_spins = 0;    // polls of the grid barrier's release word before a workgroup gives up (0: the default)
   int nqkv() const { return (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim; }
   int qdim() const { return d.n_q_heads * d.head_dim; }
   int kvdim() const { return d.n_kv_heads * d.head_dim; }
@@ -75,7 +83,7 @@ struct la_kv {
   bool v_blocked = false;  // V stored in the MFMA path's key-blocked layout
   void *K = nullptr, *V = nullptr;  // [n_layers][max_len][Hkv][dh] (V: see v_blocked)
   int32_t *L_dev = nullptr;         // committed length, on the device
-  int32_t *err_dev = nullptr;       // sticky device-side range error flag
+  int32_t *err_dev = nullptr;       // the model's device error word (not owned)
   int L_bound = 0;                  // host-side upper bound on L
   size_t layer_elems() const { return (size_t)rows_alloc * m->d.n_kv_heads * m->d.head_dim; }
 };
@@ -88,6 +96,16 @@ struct la_pool {
 };
 
 namespace la {
+// Non-blocking: reports (once) an error that a kernel of an earlier launch on this model stored to its host word.
+int pending_error(const la_model *m);
+// Clears the error word and the barrier words on `s` after an error was reported, so that the next launch starts clean.
+int recover_if_needed(la_model *m, hipStream_t s);
+#define LA_PENDING(m)                     \
+  do {                                    \
+    int rc__ = la::pending_error(m);      \
+    if (rc__) return rc__;                \
+  } while (0)
+
 // generic path (la_generic.hip)
 int generic_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32_t *pos,
                     const uint64_t *vis, la_kv *kv, hipStream_t s);
@@ -106,6 +124,7 @@ int mfma_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32
                  const uint64_t *vis, la_kv *kv, hipStream_t s);
 int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                         hipStream_t s);
+void mfma_reset_sync(la_model *m, hipStream_t s);
 int mfma_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                                 hipStream_t s);
 }  // namespace la

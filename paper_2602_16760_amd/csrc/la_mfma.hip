@@ -15,6 +15,10 @@ extern template int launch_rstack_kernel<1, 4>(const StackArgs &, int, hipStream
 extern template int launch_rstack_kernel<2, 4>(const StackArgs &, int, hipStream_t);
 extern template int launch_rstack_kernel<3, 4>(const StackArgs &, int, hipStream_t);
 extern template int launch_rstack_kernel<4, 4>(const StackArgs &, int, hipStream_t);
+extern template int prepare_rstack_kernel<1, 4>(int, int);
+extern template int prepare_rstack_kernel<2, 4>(int, int);
+extern template int prepare_rstack_kernel<3, 4>(int, int);
+extern template int prepare_rstack_kernel<4, 4>(int, int);
 }  // namespace rs
 constexpr int R_NW = 4;  // MFMA waves of the register-streaming kernel
 
@@ -22,6 +26,10 @@ extern template int launch_stack_kernel<1>(const StackArgs &, int, hipStream_t);
 extern template int launch_stack_kernel<2>(const StackArgs &, int, hipStream_t);
 extern template int launch_stack_kernel<3>(const StackArgs &, int, hipStream_t);
 extern template int launch_stack_kernel<4>(const StackArgs &, int, hipStream_t);
+extern template int prepare_stack_kernel<1>(int, int);
+extern template int prepare_stack_kernel<2>(int, int);
+extern template int prepare_stack_kernel<3>(int, int);
+extern template int prepare_stack_kernel<4>(int, int);
 
 // ---- weight packing (once, at model set-up) -----------------------------------------------------
 // Destination: the per-CU streams.  Source column of packed column pc of a GEMM:
@@ -143,7 +151,7 @@ struct MfmaModel {
   Top *un_part = nullptr;
   int un_parts_per_cu = 0;
   unsigned *sync = nullptr;
-  int32_t *zero_len = nullptr;  // {0, scratch error word}: the unembedding has no cache to overflow
+  int32_t *zero_len = nullptr;  // a cache length of 0: the unembedding has no cache to overflow
   unsigned epoch = 0;
   unsigned long long *trace = nullptr;  // LA_TRACE=1: per-phase timestamps, printed after each launch
   int trace_phases = 0;
@@ -192,6 +200,12 @@ void mfma_destroy(la_model *m) {
   m->mf = nullptr;
 }
 
+void mfma_reset_sync(la_model *m, hipStream_t s) {
+  MfmaModel *f = m->mf;
+  zero_u32_kernel<<<ceil_div(SYNC_STRIDE * 66, 256), 256, 0, s>>>(f->sync, SYNC_STRIDE * 66);
+  f->epoch = 0;
+}
+
 static int na_setup(int device);  // address of the static scratch array on this device (defined with its entry point below)
 
 int mfma_create(la_model *m) {
@@ -210,6 +224,13 @@ int mfma_create(la_model *m) {
   f->use_r = env_int("LA_LDS_RING", 0) == 0;
   LA_REQUIRE((size_t)prop.sharedMemPerBlockOptin >= (size_t)LDS_BYTES || (size_t)prop.maxSharedMemoryPerMultiProcessor >= (size_t)LDS_BYTES,
              LA_EINVAL, "the device offers less LDS per workgroup than the %d bytes the kernel needs", LDS_BYTES);
+  {  // co-residency of the grid: the barrier would otherwise wait for workgroups that cannot start
+    int rc = f->use_r ? rs::prepare_rstack_kernel<1, R_NW>(f->n_wgs, cus) : prepare_stack_kernel<1>(f->n_wgs, cus);
+    if (!rc) rc = f->use_r ? rs::prepare_rstack_kernel<2, R_NW>(f->n_wgs, cus) : prepare_stack_kernel<2>(f->n_wgs, cus);
+    if (!rc) rc = f->use_r ? rs::prepare_rstack_kernel<3, R_NW>(f->n_wgs, cus) : prepare_stack_kernel<3>(f->n_wgs, cus);
+    if (!rc) rc = f->use_r ? rs::prepare_rstack_kernel<4, R_NW>(f->n_wgs, cus) : prepare_stack_kernel<4>(f->n_wgs, cus);
+    if (rc) return rc;
+  }
   int qd = m->qdim(), nqkv = m->nqkv(), g = d.n_q_heads / d.n_kv_heads;
   f->p_qkv = make_plan(nqkv, d.d_model, f->n_wgs);
   f->p_o = make_plan(d.d_model, qd, f->n_wgs);
@@ -250,12 +271,14 @@ int mfma_create(la_model *m) {
   LA_HIP(hipMemset(f->qf, 0, (size_t)d.n_kv_heads * QR * d.head_dim * 2));
   LA_HIP(hipMemset(f->sync, 0, (size_t)n_sync * 4));
   LA_HIP(hipMemset(f->zero_len, 0, 8));
+#ifdef LA_EXPERIMENTS
   if (env_int("LA_TRACE", 0)) {
     f->trace_phases = 2 + 5 * d.n_layers;
     f->trace = (unsigned long long *)dalloc(((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs) * 8);
     LA_REQUIRE(f->trace != nullptr, LA_ENOMEM, "device allocation failed");
     LA_HIP(hipMemset(f->trace, 0, ((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs) * 8));
   }
+#endif
   return LA_OK;
 }
 
@@ -366,6 +389,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     }
   }
   if (rc) return rc;
+#ifdef LA_EXPERIMENTS
   if (a.trace) {  // debugging aid: timeline of workgroup 0 (100 MHz clock) and producer statistics
     int np = n_barriers + 1;
     std::vector<unsigned long long> h((size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG * f->n_wgs);
@@ -496,6 +520,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       }
     }
   }
+#endif
   return LA_OK;
 }
 
@@ -534,7 +559,12 @@ static StackArgs base_stack_args(la_model *m, int Bp) {
   a.rsq = f->rsq;
   a.cs = m->rope_cs;
   a.sync = f->sync;
+  a.err = m->err_dev;
+  a.err_map = m->err_map;
+  a.spin_global = m->barrier_spins ? m->barrier_spins : SPIN_GLOBAL;
+#ifdef LA_EXPERIMENTS
   a.dbg = env_int("LA_DBG", 0);
+#endif
   a.pace = (unsigned)env_int("LA_PACE", 700);
   a.qkv = dev_plan(f->p_qkv);
   a.o = dev_plan(f->p_o);
@@ -565,7 +595,6 @@ int mfma_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32
   a.layer_elems = kv->layer_elems();
   a.L_dev = kv->L_dev;
   a.max_len = kv->max_len;
-  a.err = kv->err_dev;
   return launch_stack("layer_stack", f, a, 5 * (le - lb), s);
 }
 
@@ -587,7 +616,6 @@ int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, 
   a.top2 = top2;
   a.L_dev = f->zero_len;
   a.max_len = LA_MAX_ROWS;
-  a.err = f->zero_len + 1;
   return launch_stack("unembed_argmax", f, a, 2, s);
 }
 

@@ -456,7 +456,7 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
   for (int l = 0; l < n_layers; ++l) {
     const unsigned seg = seg_first + (unsigned)l * seg_stride;
     for (int e = 0; e < n_ent; ++e) {
-      if (a.trace && l == 1 && e < 16 && w < 4) {  // (timeline: when each of the first four MFMA waves starts each body of the second layer; low clock word)
+      if (LA_TRACE_PTR(a) && l == 1 && e < 16 && w < 4) {  // (timeline: when each of the first four MFMA waves starts each body of the second layer; low clock word)
         const unsigned long long t = wall_clock64();
         if (lane == 0) ctl_write(misc + M_BYTES + NW * TAB_BYTES + 4u * (unsigned)(16 * w + e), (unsigned)t);
       }
@@ -551,8 +551,8 @@ __device__ __forceinline__ bool io_grid_sync(const StackArgs &a, Io &io, unsigne
     bool ok = true;
     while ((int)(__hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
       __builtin_amdgcn_s_sleep(1);
-      if (++spins > SPIN_GLOBAL) {
-        __hip_atomic_fetch_or(a.err, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > a.spin_global) {
+        raise_error(a, 4);
         ok = false;
         break;
       }
@@ -878,7 +878,7 @@ __device__ __forceinline__ bool io_pass(const StackArgs &a, Io &io, const Pass &
   const unsigned long long t_a = io.tr ? wall_clock64() : 0ull;
   RowStat<MT, NIO> rs;
   if (rsq_in) row_factors_load<MT, NIO>(io, rsq_in, a.Bp, a.ncg, rs);
-  if (!load_operand<MT, NW>(io, A, p.KT, a_seq, a.dbg)) return false;
+  if (!load_operand<MT, NW>(io, A, p.KT, a_seq, LA_DBG_BITS(a.dbg))) return false;
   if (io.tr && io.v == 0 && io.lane == 0 && p.pidx == 0) io.tr[3] = wall_clock64() - t_a;  // (reported as "waited for weights": the operand's way in)
   if (rsq_in) row_factors_finish<MT, NIO>(io, a.Bp, a.inv_d, a.eps, rs);
   for (int w = 0; w < NW; ++w)
@@ -1208,7 +1208,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
   int ph = 0;  // phase number as in la_stack.h: first operand, then five per layer
   auto set_phase = [&](int k) {
     ph = k;
-    io.tr = (a.trace && blockIdx.x == 0 && k < a.trace_phases) ? a.trace + TRACE_SLOTS * k : nullptr;
+    io.tr = (LA_TRACE_PTR(a) && blockIdx.x == 0 && k < a.trace_phases) ? LA_TRACE_PTR(a) + TRACE_SLOTS * k : nullptr;
     io_mark(io, 0);
   };
   set_phase(0);
@@ -1326,10 +1326,10 @@ template <int MT, int NW>
 __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds_generic[];
   const lds_t lds = (lds_t)lds_generic;
-  if (a.trace && blockIdx.x == 0 && threadIdx.x == 0) a.trace[13] = wall_clock64();  // (timeline: kernel entry)
+  if (LA_TRACE_PTR(a) && blockIdx.x == 0 && threadIdx.x == 0) LA_TRACE_PTR(a)[13] = wall_clock64();  // (timeline: kernel entry)
   const int L = uni(*a.L_dev);
   if (L < 0 || L + a.Bp > a.max_len) {  // every workgroup takes the same exit: no barrier is left waiting
-    if (blockIdx.x == 0 && threadIdx.x == 0) *a.err = 1;
+    if (blockIdx.x == 0 && threadIdx.x == 0) raise_error(a, 1);
     return;
   }
   if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + NW * Lay<MT, NW>::REG + M_CTL))[threadIdx.x] = 0u;
@@ -1339,25 +1339,39 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
     build_schedule<NW>(a, Geo<MT>::NTMAX, (int)threadIdx.x - (WG_THREADS - NW),
                        lds0 + NW * Lay<MT, NW>::REG + M_BYTES + (threadIdx.x - (WG_THREADS - NW)) * TAB_BYTES);
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
-  if (a.trace && blockIdx.x == 0 && threadIdx.x == 0) a.trace[14] = wall_clock64();  // (timeline: schedules written)
+  if (LA_TRACE_PTR(a) && blockIdx.x == 0 && threadIdx.x == 0) LA_TRACE_PTR(a)[14] = wall_clock64();  // (timeline: schedules written)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (wave < NW) {
     mfma_wave_main<MT, NW>(a, lds0, wave, lane);
-    if (a.trace && lane == 0 && (blockIdx.x == 0 || blockIdx.x == 200)) a.trace[16 + (blockIdx.x ? 8 : 0) + wave] = wall_clock64();
-    if (a.trace && lane == 0 && blockIdx.x > 2) a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + wave] = wall_clock64();
+    if (LA_TRACE_PTR(a) && lane == 0 && (blockIdx.x == 0 || blockIdx.x == 200)) LA_TRACE_PTR(a)[16 + (blockIdx.x ? 8 : 0) + wave] = wall_clock64();
+    if (LA_TRACE_PTR(a) && lane == 0 && blockIdx.x > 2) LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + wave] = wall_clock64();
   } else {
     io_wave_main<MT, NW>(a, lds0, wave - NW, lane, L);
     // a wait that gave up anywhere in the workgroup: tell the host
     if (lane == 0 && ctl_read(lds0 + NW * Lay<MT, NW>::REG + M_CTL + 4 * K_DEAD) != 0)
-      __hip_atomic_fetch_or(a.err, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (a.trace && lane == 0 && (blockIdx.x == 0 || blockIdx.x == 200)) a.trace[16 + (blockIdx.x ? 8 : 0) + wave] = wall_clock64();  // (timeline: when each wave ends)
-    if (a.trace && lane == 0 && blockIdx.x > 2) a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + wave] = wall_clock64();
-    if (a.trace && wave == 7 && blockIdx.x == 0) {  // (timeline of MFMA wave 0: LDS -> the workgroup's trace words; the MFMA waves finish before the last epilogue)
+      raise_error(a, 4);
+    if (LA_TRACE_PTR(a) && lane == 0 && (blockIdx.x == 0 || blockIdx.x == 200)) LA_TRACE_PTR(a)[16 + (blockIdx.x ? 8 : 0) + wave] = wall_clock64();  // (timeline: when each wave ends)
+    if (LA_TRACE_PTR(a) && lane == 0 && blockIdx.x > 2) LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + wave] = wall_clock64();
+    if (LA_TRACE_PTR(a) && wave == 7 && blockIdx.x == 0) {  // (timeline of MFMA wave 0: LDS -> the workgroup's trace words; the MFMA waves finish before the last epilogue)
       const unsigned v = ctl_read_lanes(lds0 + NW * Lay<MT, NW>::REG + M_BYTES + NW * TAB_BYTES + 4u * (unsigned)lane);
-      a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG + lane] = v;  // (the words of workgroups 1 and 2, which leave theirs alone)
+      LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG + lane] = v;  // (the words of workgroups 1 and 2, which leave theirs alone)
     }
   }
+}
+
+// Run once per model: raises the kernel's LDS limit and checks that n_wgs workgroups can be resident at once on `cus`
+// compute units (the grid barrier waits for all of them; what other work shares the GPU is the caller's concern).
+template <int MT, int NW>
+int prepare_rstack_kernel(int n_wgs, int cus) {
+  constexpr int bytes = lds_bytes<MT, NW>();
+  LA_HIP(hipFuncSetAttribute((const void *)rstack_kernel<MT, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  int per_cu = 0;
+  LA_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, rstack_kernel<MT, NW>, WG_THREADS, bytes));
+  LA_REQUIRE(per_cu >= 1 && n_wgs <= per_cu * cus, LA_EINVAL,
+             "the persistent kernel for %d row tiles cannot keep %d workgroups resident (%d per compute unit on %d units)", MT, n_wgs,
+             per_cu, cus);
+  return LA_OK;
 }
 
 template <int MT, int NW>

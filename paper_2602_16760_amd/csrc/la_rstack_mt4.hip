@@ -3,5 +3,6 @@
 namespace la {
 namespace rs {
 template int launch_rstack_kernel<4, 4>(const StackArgs &, int, hipStream_t);
+template int prepare_rstack_kernel<4, 4>(int, int);
 }
 }  // namespace la

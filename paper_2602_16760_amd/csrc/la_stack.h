@@ -117,6 +117,16 @@ __device__ __forceinline__ Top top_merge2(Top a, Top b) {
 
 enum GemmMode { MODE_QKV = 0, MODE_RESID = 1, MODE_GATEUP = 2, MODE_UNEMBED = 3 };
 
+// Timelines (StackArgs::trace) and timing experiments (StackArgs::dbg, which make results wrong) exist only in a build
+// with -DLA_EXPERIMENTS; in the default build every test of them is a compile-time constant and the code is dropped.
+#ifdef LA_EXPERIMENTS
+#define LA_TRACE_PTR(a) ((a).trace)
+#define LA_DBG_BITS(x) (x)
+#else
+#define LA_TRACE_PTR(a) ((unsigned long long *)nullptr)
+#define LA_DBG_BITS(x) 0
+#endif
+
 struct GemmDev {
   int KT;      // k-tiles (32 deep)
   int ntiles;  // 16-column tiles of the whole matrix
@@ -155,7 +165,9 @@ struct StackArgs {
   size_t layer_elems;
   const int32_t *L_dev;
   int max_len;
-  int32_t *err;
+  int32_t *err;      // device error word: 1 the block does not fit the cache, 4 a grid barrier gave up
+  int32_t *err_map;  // mapped host word that receives the same code (plain store), read by the host without synchronising
+  unsigned spin_global;  // polls of the barrier's release word before a workgroup gives up
   const float *g_final;
   Top *un_part;
   int un_parts_per_cu;
@@ -168,6 +180,12 @@ struct StackArgs {
   int trace_seg;              // which weight matrix of the second layer the producer's eight snapshots cover (0 QKV, 1 O, 2 gate / up, 3 down)
   int trace_sel;              // every workgroup records when it reaches the barriers that end phases trace_sel .. trace_sel + 7
 };
+
+// Raises an error: ORs the code into the device word and stores it to the host's mapped word.
+__device__ __forceinline__ void raise_error(const StackArgs &a, int code) {
+  __hip_atomic_fetch_or(a.err, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(a.err_map, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 // Values that are the same in every lane, moved to scalar registers.  The compiler cannot see
 // that words read from LDS or memory are wave-uniform; without this it guards loads with
@@ -373,8 +391,8 @@ __device__ __forceinline__ bool grid_sync(const StackArgs &a, Wave &wv, unsigned
       bool ok = true;
       while ((int)(__hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
         __builtin_amdgcn_s_sleep(1);
-        if (++spins > SPIN_GLOBAL) {
-          __hip_atomic_fetch_or(a.err, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (++spins > a.spin_global) {
+          raise_error(a, 4);
           ok = false;
           break;
         }
@@ -412,7 +430,7 @@ __device__ __forceinline__ void producer(const StackArgs &a, unsigned ctl, LDS_A
   unsigned long long t_wait = 0, t_poll = 0;
   constexpr bool tr = TR;
   const unsigned long long t_begin = tr ? wall_clock64() : 0ull;
-  if (a.dbg & 1) {
+  if (LA_DBG_BITS(a.dbg) & 1) {
     ctl_write(ctl + 4 * C_LANDED, total);
     return;
   }
@@ -816,8 +834,8 @@ __device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveS
 
   u32x4 rA[DA][MT];
   auto load_a = [&](int slot, int i) {
-    unsigned vo = (i < nk && !(lc.dbg & 4)) ? voff : OOB;  // out of range: zeros come back, no memory traffic
-    unsigned kt = (lc.dbg & 2) ? 0u : (unsigned)(w + NCW * i);
+    unsigned vo = (i < nk && !(LA_DBG_BITS(lc.dbg) & 4)) ? voff : OOB;  // out of range: zeros come back, no memory traffic
+    unsigned kt = (LA_DBG_BITS(lc.dbg) & 2) ? 0u : (unsigned)(w + NCW * i);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) rA[slot][mt] = __builtin_amdgcn_raw_buffer_load_b128(ra, vo, (kt * MT + mt) * 1024u, 0);
   };
@@ -952,7 +970,7 @@ __device__ __attribute__((noinline)) WaveState gemm_pass(unsigned lds0_in, WaveS
       e.LDT = LDT;
       e.part = p.part0 + c0 / TPC;
       e.tid = w * 64 + lane;
-      if (!(lc.dbg & 8)) gemm_epilogue(e);
+      if (!(LA_DBG_BITS(lc.dbg) & 8)) gemm_epilogue(e);
     }
     // everyone has finished reading the tile before the buffers are written again
     if (c0 == 0 && tile0 == 0) tr_mark(tr, wv, 5);
@@ -1375,14 +1393,14 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   const lds_t lds = (lds_t)lds_generic;
   const int L = uni(*a.L_dev);
   if (L < 0 || L + a.Bp > a.max_len) {  // every workgroup takes the same exit: no barrier is left waiting
-    if (blockIdx.x == 0 && threadIdx.x == 0) *a.err = 1;
+    if (blockIdx.x == 0 && threadIdx.x == 0) raise_error(a, 1);
     return;
   }
   if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + LDS_CTL))[threadIdx.x] = 0u;
   if (threadIdx.x == 64) {
     LDS_AS LaunchConst *c = (LDS_AS LaunchConst *)(lds + LDS_CONST);
-    c->Bp = a.Bp; c->MT = MT; c->d = a.d; c->ncg = a.ncg; c->Hq = a.Hq; c->Hkv = a.Hkv; c->dh = a.dh; c->L = L; c->dbg = a.dbg;
-    c->x_lds = (a.mode == 0 && my_tiles(a.o.ntiles) * MT <= X_TILES && !(a.dbg & 128)) ? 1 : 0;
+    c->Bp = a.Bp; c->MT = MT; c->d = a.d; c->ncg = a.ncg; c->Hq = a.Hq; c->Hkv = a.Hkv; c->dh = a.dh; c->L = L; c->dbg = LA_DBG_BITS(a.dbg);
+    c->x_lds = (a.mode == 0 && my_tiles(a.o.ntiles) * MT <= X_TILES && !(LA_DBG_BITS(a.dbg) & 128)) ? 1 : 0;
     c->inv_d = a.inv_d; c->eps = a.eps; c->x = a.x; c->cs = a.cs; c->qf = a.qf;
   }
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
@@ -1397,7 +1415,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
 
   if (wave == NCW) {
     __builtin_amdgcn_s_setprio(3);  // the producer's few instructions go first on its SIMD (4 % on a one-row step)
-    unsigned long long *st = a.trace ? a.trace + TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x : nullptr;
+    unsigned long long *st = LA_TRACE_PTR(a) ? LA_TRACE_PTR(a) + TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x : nullptr;
     // (timeline: producer snapshots at the start and the end of the second layer's gate / up weights)
     // (timeline: which of the second layer's four weight matrices the snapshots cover: 0 QKV, 1 O, 2 gate / up, 3 down)
     const unsigned seg0 = a.trace_seg == 0 ? 0u : a.trace_seg == 1 ? f_qkv : a.trace_seg == 3 ? f_qkv + f_o + f_gu : f_qkv + f_o;
@@ -1427,18 +1445,18 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
   const int n_phases = a.mode == 1 ? 3 : 1 + 5 * (a.le - a.lb);
   const bool x_lds = launch_const(lds0).x_lds != 0;
   const int n_rt = a.Hq / a.Hkv * MT, n_units = a.Hkv * n_rt;
-  const int att_first = (a.dbg & 32) ? 0 : att_first_wg(a.qkv.ntiles, n_units);
+  const int att_first = (LA_DBG_BITS(a.dbg) & 32) ? 0 : att_first_wg(a.qkv.ntiles, n_units);
   const int att_u0 = (int)blockIdx.x >= att_first ? (int)blockIdx.x - att_first : n_units;  // no unit: n_units
   unsigned sbase = 0;
   unsigned long long *tr = nullptr;  // timeline slots of the current phase (workgroup 0 only)
   for (int ph = 0; ph < n_phases; ++ph) {
     if (ph > 0) {
       const int k = ph - 1 - a.trace_sel;
-      if (a.trace && k >= 0 && k < 8 && wv.w == 0 && wv.lane == 0)
-        a.trace[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + 8 + k] = wall_clock64();
+      if (LA_TRACE_PTR(a) && k >= 0 && k < 8 && wv.w == 0 && wv.lane == 0)
+        LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + 8 + k] = wall_clock64();
       if (!grid_sync(a, wv, ++epoch, tr)) return;
     }
-    tr = (a.trace && blockIdx.x == 0 && ph < a.trace_phases) ? a.trace + TRACE_SLOTS * ph : nullptr;
+    tr = (LA_TRACE_PTR(a) && blockIdx.x == 0 && ph < a.trace_phases) ? LA_TRACE_PTR(a) + TRACE_SLOTS * ph : nullptr;
     tr_mark(tr, wv, 0);
     if (tr && wv.w == 0 && wv.lane == 0) tr[12] = clock64();  // shader clock, to report the running frequency
     const int sub = a.mode == 1 ? (ph == 0 ? 0 : ph == 1 ? 6 : 7) : (ph == 0 ? 0 : 1 + (ph - 1) % 5);
@@ -1470,11 +1488,11 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
         g = a.qkv; have_g = true; frags = f_qkv;
         break;
       case 2:
-        if (att_u0 < n_units || (a.dbg & 64)) {  // (a call costs the callee's register saves: only where there is work)
+        if (att_u0 < n_units || (LA_DBG_BITS(a.dbg) & 64)) {  // (a call costs the callee's register saves: only where there is work)
           AttArgs t;
           t.Kc = Kc; t.Vc = Vc; t.attn_out = attn_l; t.vis = a.vis; t.lds0 = lds0; t.u0 = att_u0;
           // (the timeline shows the attention of the workgroup that runs unit 0)
-          t.tr = (a.trace && att_u0 == 0 && ph < a.trace_phases) ? a.trace + TRACE_SLOTS * ph : nullptr;
+          t.tr = (LA_TRACE_PTR(a) && att_u0 == 0 && ph < a.trace_phases) ? LA_TRACE_PTR(a) + TRACE_SLOTS * ph : nullptr;
           wv.st = a.dh == 128 ? attention_phase<128>(t, wv.st) : attention_phase<64>(t, wv.st);
           wv.st.ok = uni(wv.st.ok);
           if (!wv.st.ok) return;
@@ -1522,7 +1540,7 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
       wv.st = gemm_phase<MT>(p, wv.st, g, lds0, wv.w);
       if (!wv.st.ok) return;
       sbase += frags;
-      if (sub == 1 && !(a.dbg & 16))
+      if (sub == 1 && !(LA_DBG_BITS(a.dbg) & 16))
         for (int u = att_u0; u < n_units; u += gridDim.x) kv_touch(Kc, Vc, u, n_rt, a.Hkv, a.dh, L, wv, lds0);
     }
     tr_mark(tr, wv, 2);
@@ -1531,6 +1549,18 @@ __global__ __launch_bounds__(WG_THREADS) void stack_kernel(StackArgs a) {
 
 // Launches the persistent kernel for MT row tiles (explicitly instantiated in la_stack_mt*.hip,
 // one translation unit per MT so that they compile in parallel).
+// Run once per model: raises the kernel's LDS limit and checks that n_wgs workgroups can be resident at once.
+template <int MT>
+int prepare_stack_kernel(int n_wgs, int cus) {
+  LA_HIP(hipFuncSetAttribute((const void *)stack_kernel<MT>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+  int per_cu = 0;
+  LA_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, stack_kernel<MT>, WG_THREADS, LDS_BYTES));
+  LA_REQUIRE(per_cu >= 1 && n_wgs <= per_cu * cus, LA_EINVAL,
+             "the persistent kernel for %d row tiles cannot keep %d workgroups resident (%d per compute unit on %d units)", MT, n_wgs,
+             per_cu, cus);
+  return LA_OK;
+}
+
 template <int MT>
 int launch_stack_kernel(const StackArgs &a, int n_wgs, hipStream_t s) {
   static bool attr_set = false;

@@ -3,4 +3,5 @@
 
 namespace la {
 template int launch_stack_kernel<3>(const StackArgs &, int, hipStream_t);
+template int prepare_stack_kernel<3>(int, int);
 }  // namespace la

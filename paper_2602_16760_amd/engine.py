@@ -89,8 +89,8 @@ class Engine:
             n = min(chunk, len(tokens) - s)
             hidden = torch.empty((n, sh.d_model), dtype=torch.float32, device="cuda")
             B.la_embed(self.model, toks[s:s + n].contiguous(), hidden)
-            pos = torch.arange(L, L + n, dtype=torch.int32, device="cuda")
-            vis = B.to_device(np.array([(1 << (i + 1)) - 1 for i in range(n)], dtype=np.uint64))
+            pos_h, vis_h = B.la_causal_layout(L, n)
+            pos, vis = B.to_device(pos_h), B.to_device(vis_h)
             B.la_forward_layers(self.model, 0, sh.n_layers, hidden, pos, vis, self.kv)
             L += n
             B.la_kv_set_len(self.kv, L)
@@ -143,5 +143,7 @@ class Engine:
                 self.step(emitted, n_new)
             done = int(n_field.item())
         st = B.read_state(self.state)
+        if st.error:
+            raise B.LaError(-4 if st.error & 4 else -3, f"a kernel raised error word {st.error} during generation")
         return emitted.cpu().numpy().astype(np.int64), dict(steps=st.steps, matched_steps=st.matched_steps,
                                                             n_emitted=st.n_emitted, L=st.L)

@@ -60,3 +60,16 @@ def test_host_argument_checks():
         B.la_lookahead_layout(2, 3, 1, 0, 1, 6)       # Bp smaller than the block
     with pytest.raises(B.LaError):
         B.la_lookahead_layout(0, 1, 2, 0, 0, 1)       # N=1 needs G=0
+
+
+@pytest.mark.parametrize("t,n", [(0, 1), (5, 7), (1000, 64), (31, 33)])
+def test_host_causal_layout_matches_oracle(t, n):
+    """Section 4.4: the plain causal mask of a run of consecutive tokens (prompt chunks)."""
+    from paper_2602_16760_amd import binding as B
+    pos, vis = B.la_causal_layout(t, n)
+    opos, ovis = ola.causal_block(t, n)
+    assert list(pos) == list(opos) and [int(v) for v in vis] == [int(v) for v in ovis]
+    with pytest.raises(B.LaError):
+        B.la_causal_layout(0, 65)
+    with pytest.raises(B.LaError):
+        B.la_causal_layout(-1, 4)

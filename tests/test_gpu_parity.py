@@ -346,6 +346,62 @@ def test_error_paths():
         eng.close()
 
 
+def test_barrier_timeout_is_reported_and_the_model_recovers():
+    """The error path of the persistent kernel, forced from the host: with the grid barrier's
+    patience set to one poll the workgroups that arrive first give up, every wave of the kernel
+    still leaves it (each wait in it is bounded and ends at once when the workgroup is marked
+    dead), the next call on the model or its cache reports LA_EHIP without having synchronised,
+    the controller state carries the code, and after the report the model works again."""
+    from paper_2602_16760_amd import binding as B
+    import torch
+    shape = synth.SHAPES["small_bf16"].with_layers(2)
+    eng = gpu_engine(shape, 128, seed=5)
+    okv = otf.KVCache(shape, 128)
+    try:
+        prefill_both(shape, eng, okv, 40, seed=2)
+        x, pos, vis = _block_inputs(shape, 40, 5, 4, 5, 32, 3, seed=6)
+        want = eng.forward(x, pos, vis)
+        h = B.to_device(x.astype(np.float32))
+        p = B.to_device(np.asarray(pos, dtype=np.int32))
+        m = B.to_device(np.asarray([int(v) for v in vis], dtype=np.uint64))
+        B.la_set_barrier_timeout(eng.model, 1)
+        B.la_forward_layers(eng.model, 0, 2, h, p, m, eng.kv)   # enqueued; fails on the device
+        torch.cuda.synchronize()
+        with pytest.raises(B.LaError) as e:
+            B.la_kv_set_len(eng.kv, 40)
+        assert e.value.code == -4 and "barrier" in str(e.value)
+        B.la_kv_set_len(eng.kv, 40)                              # reported once
+        # the same failure, seen through the controller state or the next call, whichever is first
+        pool = B.la_pool_alloc(shape.vocab, 4, 5)
+        state = B.new_state()
+        B.la_state_init(pool, eng.kv, 5, 4, 5, B.to_device(np.arange(41, dtype=np.int32)), 32, True, state)
+        ids = torch.zeros(32, dtype=torch.int32, device="cuda")
+        out = torch.zeros(8, dtype=torch.int32, device="cuda")
+        B.la_forward_layers(eng.model, 0, 2, h, p, m, eng.kv)
+        try:
+            B.la_ngram_accept(pool, eng.kv, 5, 4, 5, ids, state, out, 8)
+            torch.cuda.synchronize()
+            assert B.read_state(state).error == 4
+            with pytest.raises(B.LaError):
+                B.la_kv_get_len(eng.kv)
+        except B.LaError as err:
+            assert err.code == -4
+        torch.cuda.synchronize()
+        try:                                                     # whatever the kernel's last workgroups still stored
+            B.la_kv_get_len(eng.kv)
+        except B.LaError as err:
+            assert err.code == -4
+        B.la_free_pool(pool)
+        # recovery: default patience, same block, same bits as before the failures
+        B.la_set_barrier_timeout(eng.model, 0)
+        B.la_kv_set_len(eng.kv, 40)
+        got = eng.forward(x, pos, vis)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        assert B.la_kv_get_len(eng.kv) == 40
+    finally:
+        eng.close()
+
+
 def _orbit_model(shape, period, seed):
     """A model whose greedy text is known in closed form: with wo = wdown = 0 the residual stream
     stays the token's embedding row, and with unembedding column perm(v) = embedding row v the
