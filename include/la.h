@@ -239,6 +239,21 @@ int la_causal_layout(int t, int n, int32_t *pos_host, uint64_t *vis_host);
  * (2^21, about two seconds).  Takes effect from the next launch on the model. */
 int la_set_barrier_timeout(la_model *m, unsigned polls);
 
+/* ---- latency model of the split deployment (host arithmetic) --------------------------- */
+
+/* Section 6.3: the wall time of a step is the network round trip plus a fixed overhead that
+ * does not depend on the network (compute on both sides, serialization).  All times in
+ * milliseconds, double precision, host pointers.  LA_EINVAL for negative times, a step
+ * shorter than its round trip, or a zero step time. */
+int la_rtt_fixed_overhead(double per_step_ms, double rtt_ms, double *fixed_ms);
+/* Section 6.3, projection model: tokens per second at round-trip time rtt_ms for a decoder
+ * that commits tokens_per_step tokens per step (1 for sequential decoding) with fixed
+ * overhead fixed_ms:  tokens_per_step / ((rtt_ms + fixed_ms) / 1000). */
+int la_rtt_project(double tokens_per_step, double rtt_ms, double fixed_ms, double *tok_per_s);
+/* Section 4.2: Jacobi decoding of a block of k tokens that converges after `iterations`
+ * round trips:  k / (iterations * rtt_ms / 1000). */
+int la_jacobi_project(int k, double iterations, double rtt_ms, double *tok_per_s);
+
 /* ---- diagnostics ---------------------------------------------------------------------- */
 
 /* Per-kernel timing with HIP events on the launch stream.  While enabled every kernel

@@ -61,6 +61,7 @@ EXPORTS = [
     "la_init_model", "la_model_set_layer", "la_free_model", "la_kv_alloc", "la_kv_set_len", "la_kv_get_len",
     "la_kv_fill", "la_kv_read", "la_free_kv", "la_embed", "la_forward_layers", "la_unembed_argmax",
     "la_unembed_argmax_noalloc", "la_causal_layout", "la_set_barrier_timeout",
+    "la_rtt_fixed_overhead", "la_rtt_project", "la_jacobi_project",
     "la_pool_alloc", "la_free_pool", "la_state_init", "la_ngram_accept", "la_lookahead_layout",
     "la_profile_enable", "la_profile_select", "la_profile_read", "la_profile_copy", "la_last_error",
 ]
@@ -94,6 +95,9 @@ def _load():
         "la_lookahead_layout": (i32, [C.POINTER(la_lookahead_desc), i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
         "la_causal_layout": (i32, [i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
         "la_set_barrier_timeout": (i32, [vp, C.c_uint]),
+        "la_rtt_fixed_overhead": (i32, [C.c_double, C.c_double, C.POINTER(C.c_double)]),
+        "la_rtt_project": (i32, [C.c_double, C.c_double, C.c_double, C.POINTER(C.c_double)]),
+        "la_jacobi_project": (i32, [i32, C.c_double, C.c_double, C.POINTER(C.c_double)]),
         "la_profile_enable": (i32, [i32]),
         "la_profile_select": (i32, [C.c_char_p]),
         "la_profile_read": (i32, [C.POINTER(la_profile_entry), i32]),
@@ -255,6 +259,24 @@ def la_causal_layout(t, n):
 
 def la_set_barrier_timeout(model, polls):
     _check(lib.la_set_barrier_timeout(model, polls))
+
+
+def la_rtt_fixed_overhead(per_step_ms, rtt_ms) -> float:
+    out = C.c_double(0.0)
+    _check(lib.la_rtt_fixed_overhead(per_step_ms, rtt_ms, C.byref(out)))
+    return out.value
+
+
+def la_rtt_project(tokens_per_step, rtt_ms, fixed_ms) -> float:
+    out = C.c_double(0.0)
+    _check(lib.la_rtt_project(tokens_per_step, rtt_ms, fixed_ms, C.byref(out)))
+    return out.value
+
+
+def la_jacobi_project(k, iterations, rtt_ms) -> float:
+    out = C.c_double(0.0)
+    _check(lib.la_jacobi_project(k, iterations, rtt_ms, C.byref(out)))
+    return out.value
 
 
 def la_profile_enable(on: bool):

@@ -491,3 +491,26 @@ extern "C" int la_causal_layout(int t, int n, int32_t *pos_host, uint64_t *vis_h
   }
   return LA_OK;
 }
+
+// ---- latency model of the split deployment (host arithmetic, double) ------------------------------
+extern "C" int la_rtt_fixed_overhead(double per_step_ms, double rtt_ms, double *fixed_ms) {
+  LA_REQUIRE(fixed_ms != nullptr, LA_EINVAL, "NULL output");
+  LA_REQUIRE(rtt_ms >= 0.0 && per_step_ms >= rtt_ms, LA_EINVAL, "a step of %g ms cannot contain a round trip of %g ms", per_step_ms, rtt_ms);
+  *fixed_ms = per_step_ms - rtt_ms;
+  return LA_OK;
+}
+
+extern "C" int la_rtt_project(double tokens_per_step, double rtt_ms, double fixed_ms, double *tok_per_s) {
+  LA_REQUIRE(tok_per_s != nullptr, LA_EINVAL, "NULL output");
+  LA_REQUIRE(tokens_per_step > 0.0 && rtt_ms >= 0.0 && fixed_ms >= 0.0 && rtt_ms + fixed_ms > 0.0, LA_EINVAL,
+             "need tokens_per_step > 0 and a positive step time (rtt %g ms + fixed %g ms)", rtt_ms, fixed_ms);
+  *tok_per_s = tokens_per_step / ((rtt_ms + fixed_ms) / 1000.0);
+  return LA_OK;
+}
+
+extern "C" int la_jacobi_project(int k, double iterations, double rtt_ms, double *tok_per_s) {
+  LA_REQUIRE(tok_per_s != nullptr, LA_EINVAL, "NULL output");
+  LA_REQUIRE(k >= 1 && iterations > 0.0 && rtt_ms > 0.0, LA_EINVAL, "need k >= 1, iterations > 0 and rtt > 0");
+  *tok_per_s = (double)k / (iterations * rtt_ms / 1000.0);
+  return LA_OK;
+}

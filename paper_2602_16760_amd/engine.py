@@ -5,6 +5,8 @@ unembedding + argmax, n-gram acceptance, KV commit, next-block build) is a libra
 """
 from __future__ import annotations
 
+import time
+
 import numpy as np
 import torch
 
@@ -147,3 +149,57 @@ class Engine:
             raise B.LaError(-4 if st.error & 4 else -3, f"a kernel raised error word {st.error} during generation")
         return emitted.cpu().numpy().astype(np.int64), dict(steps=st.steps, matched_steps=st.matched_steps,
                                                             n_emitted=st.n_emitted, L=st.L)
+
+    # -- the split deployment on one GPU, with an injected round trip ---------------------------------
+    def step_split(self, emitted: torch.Tensor, max_total: int, head_layers: int, tail_layers: int, rtt_ms: float):
+        """One decode step cut where the paper cuts the model (Section 3.1): the first
+        `head_layers` and the last `tail_layers` layers are the local half, the layers between
+        them the cloud half; the hidden states cross the cut twice per step, and each crossing
+        costs half of rtt_ms here (a host sleep after the stream has drained, as a network would
+        make the next half wait).  Returns (local_ms, cloud_ms) of GPU time, by host clock."""
+        W, N, G = self.la
+        n = self.shape.n_layers
+        t0 = time.perf_counter()
+        B.la_embed(self.model, self._tok, self._hidden)
+        B.la_forward_layers(self.model, 0, head_layers, self._hidden, self._pos, self._vis, self.kv)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        time.sleep(rtt_ms / 2000.0)
+        t2 = time.perf_counter()
+        B.la_forward_layers(self.model, head_layers, n - tail_layers, self._hidden, self._pos, self._vis, self.kv)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        time.sleep(rtt_ms / 2000.0)
+        t4 = time.perf_counter()
+        B.la_forward_layers(self.model, n - tail_layers, n, self._hidden, self._pos, self._vis, self.kv)
+        B.la_unembed_argmax(self.model, self._hidden, self._ids, self._top2)
+        B.la_ngram_accept(self.pool, self.kv, W, N, G, self._ids, self.state, emitted, max_total)
+        torch.cuda.synchronize()
+        t5 = time.perf_counter()
+        return ((t1 - t0) + (t5 - t4)) * 1e3, (t3 - t2) * 1e3
+
+    def generate_split(self, prompt: np.ndarray, n_new: int, W: int, N: int, G: int, head_layers: int, tail_layers: int,
+                       rtt_ms: float, Bp: int | None = None, seed_pool: bool = True):
+        """Greedy generation through step_split.  Returns (tokens, stats): steps, tokens per
+        step, wall milliseconds per step, local and cloud GPU milliseconds per step, and the
+        measured throughput, from which la_rtt_fixed_overhead / la_rtt_project give the paper's
+        decomposition and projection (Section 6.3)."""
+        rows = 1 + (W + G) * (N - 1)
+        Bp = rows if Bp is None else Bp
+        self.start(prompt, W, N, G, Bp, seed_pool)
+        emitted = torch.zeros(n_new, dtype=torch.int32, device="cuda")
+        n_field = B.state_field(self.state, "n_emitted")
+        steps, local, cloud = 0, 0.0, 0.0
+        t0 = time.perf_counter()
+        while int(n_field.item()) < n_new:
+            l, c = self.step_split(emitted, n_new, head_layers, tail_layers, rtt_ms)
+            local += l
+            cloud += c
+            steps += 1
+        wall = (time.perf_counter() - t0) * 1e3
+        st = B.read_state(self.state)
+        if st.error:
+            raise B.LaError(-4 if st.error & 4 else -3, f"a kernel raised error word {st.error} during generation")
+        return emitted.cpu().numpy().astype(np.int64), dict(
+            steps=steps, tokens_per_step=n_new / steps, ms_per_step=wall / steps, local_ms=local / steps,
+            cloud_ms=cloud / steps, tok_per_s=n_new / (wall / 1e3), matched_steps=st.matched_steps)

@@ -459,6 +459,39 @@ def test_closed_form_periodic_text_reaches_n_tokens_per_step(name):
         eng.close()
 
 
+def test_split_generation_with_injected_round_trip_follows_the_latency_model():
+    """Section 3.1 / 6.3 on one GPU: the model cut into a local head, a cloud middle and a local
+    tail (layer ranges of la_forward_layers) gives the same tokens as the uncut model, and with
+    a round trip injected between the halves the measured throughput is the one the paper's
+    model projects from the tokens per step and the fixed overhead measured without it."""
+    from paper_2602_16760_amd.engine import Engine
+    from paper_2602_16760_amd import binding as B
+    shape = synth.SHAPES["small_bf16"]
+    period, W, N, G, n_new = 5, 5, 4, 5, 48
+    perm, layer, head = _orbit_model(shape, period, 4)
+    prompt = [3 * period + 2]
+    for _ in range(3 * period + 1):
+        prompt.append(int(perm[prompt[-1]]))
+    prompt = np.asarray(prompt, dtype=np.int32)
+    eng = Engine(shape, 256, layer, head)
+    try:
+        whole, st = eng.generate(prompt, n_new, W, N, G, Bp=32)
+        eng.generate_split(prompt, n_new, W, N, G, 1, 1, 0.0, Bp=32)              # warm-up
+        t0, s0 = eng.generate_split(prompt, n_new, W, N, G, 1, 1, 0.0, Bp=32)
+        rtt_ms = 6.0
+        t1, s1 = eng.generate_split(prompt, n_new, W, N, G, 1, 1, rtt_ms, Bp=32)
+        assert np.array_equal(t0, whole) and np.array_equal(t1, whole)
+        assert s0["steps"] == st["steps"] == s1["steps"] and s1["tokens_per_step"] > 2.0
+        fixed = B.la_rtt_fixed_overhead(s0["ms_per_step"], 0.0)
+        want = B.la_rtt_project(s1["tokens_per_step"], rtt_ms, fixed)
+        print(f"fixed overhead {fixed:.3f} ms/step (local {s0['local_ms']:.3f}, cloud {s0['cloud_ms']:.3f}); at {rtt_ms} ms: "
+              f"projected {want:.1f} tok/s, measured {s1['tok_per_s']:.1f}")
+        assert abs(s1["tok_per_s"] - want) / want <= 0.15   # the paper's own cross-validation error is up to 6.2 %
+        assert s1["ms_per_step"] >= rtt_ms
+    finally:
+        eng.close()
+
+
 @pytest.mark.parametrize("name,Bp", [("small_bf16", 32), ("small64_bf16", 17)])
 def test_teacher_forced_steps_over_relocated_rows(name, Bp):
     """Twenty real steps (embedding gather, layer stack, accept with cache relocation) with the ids
