@@ -222,6 +222,27 @@ int la_state_init(la_pool *p, la_kv *kv, const la_lookahead_desc *la, const int3
 int la_ngram_accept(la_pool *p, la_kv *kv, const la_lookahead_desc *la, const int32_t *ids,
                     la_step_state *state, int32_t *emitted, int max_total, void *stream);
 
+/* ---- Jacobi decoding (Section 4.2) ---------------------------------------------------- */
+
+/* Jacobi parallel decoding with the same five step calls, the controller swapped: a block of
+ * k future positions is guessed (first guess: the last committed token), every pass runs the
+ * rows {c0, y_1, .., y_(k-1)} at positions L.. under the plain causal mask (Section 4.4)
+ * through la_embed / la_forward_layers / la_unembed_argmax, and la_jacobi_accept replaces the
+ * guesses by the pass's arg-max ids.  The block has converged when a pass returns the guesses
+ * it was given, and after k passes at the latest (pass j makes guess j final); it then commits
+ * k tokens (never more than max_total - state->n_emitted): they go to emitted[], L advances
+ * over the pass's cache rows, which were computed from the final tokens, and a new block starts.
+ * la_step_state in this mode: n_cand = k, cand[0..k-1] = the guesses, steps = passes so far,
+ * matched_steps = blocks committed, last_emitted = tokens the last pass committed (0 while the
+ * block still moves), last_k = passes spent on the current block, last_m = passes the last
+ * committed block took; tok/pos/vis = the next pass (rows k..Bp-1 see only themselves).
+ * la_jacobi_init also sets the cache length to P-1, like la_state_init.
+ * LA_EINVAL: k outside 1..Bp, Bp > LA_MAX_ROWS, NULL pointer; LA_ERANGE: P - 1 + Bp > max_len. */
+int la_jacobi_init(la_kv *kv, int k, const int32_t *prompt, int P, int Bp, la_step_state *state,
+                   void *stream);
+int la_jacobi_accept(la_kv *kv, int k, const int32_t *ids, la_step_state *state, int32_t *emitted,
+                     int max_total, void *stream);
+
 /* Host helper: positions and visibility masks of a lookahead block whose row 0 sits at
  * position t with n_cand candidates present (no tokens involved).  pos_host [Bp],
  * vis_host [Bp] are host arrays. */

@@ -199,6 +199,75 @@ __global__ void accept_kernel(PoolView p, la_step_state *st, const int32_t *ids,
   build_block(st, W, N, G);
 }
 
+// ---- Jacobi decoding (Section 4.2) --------------------------------------------------------------
+// The block's rows: row 0 = c0 at position L, row i = guess y_i at L + i (i < k) under the plain
+// causal mask; rows k.. carry nothing.  The guesses live in st->cand[0..k-1].
+__device__ void jacobi_build(la_step_state *st, int k) {
+  const int Bp = st->Bp, t = st->L;
+  for (int i = 0; i < Bp; ++i) {
+    if (i < k) {
+      st->tok[i] = i == 0 ? st->c0 : st->cand[i - 1];
+      st->pos[i] = t + i;
+      st->vis[i] = i == 63 ? ~0ull : ((1ull << (i + 1)) - 1ull);
+    } else {
+      st->tok[i] = 0;
+      st->pos[i] = t + k - 1;
+      st->vis[i] = 1ull << i;
+    }
+  }
+}
+
+__global__ void jacobi_init_kernel(la_step_state *st, const int32_t *prompt, int P, int k, int Bp, int32_t *kv_L) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->L = P - 1;
+  st->c0 = prompt[P - 1];
+  st->Bp = Bp;
+  st->n_cand = k;
+  st->steps = st->matched_steps = st->n_emitted = st->last_emitted = st->last_k = st->last_m = 0;
+  st->error = st->reserved = 0;
+  for (int i = 0; i < k; ++i) st->cand[i] = st->c0;  // every position starts from the last committed token
+  jacobi_build(st, k);
+  *kv_L = P - 1;
+}
+
+// One pass's greedy ids become the new guesses (ids[i] is the prediction for position L + i + 1).  The block has
+// converged when the pass returned its own input, and after k passes at the latest (pass j fixes guess j for good);
+// it then commits: the pass's cache rows L.. were computed from the final tokens, so they stay and L advances.
+__global__ void jacobi_accept_kernel(la_step_state *st, const int32_t *ids, int32_t *emitted, int max_total, int k,
+                                     int32_t *kv_L, const int32_t *err) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  st->error = *err;
+  int remaining = max_total - st->n_emitted;
+  if (remaining <= 0) {
+    st->last_emitted = 0;
+    return;
+  }
+  bool same = true;
+  for (int i = 0; i < k; ++i) {
+    same = same && (ids[i] == st->cand[i]);
+    st->cand[i] = ids[i];
+  }
+  st->steps += 1;
+  st->last_k += 1;
+  if (!same && st->last_k < k) {
+    st->last_emitted = 0;
+    jacobi_build(st, k);
+    return;
+  }
+  int e = k < remaining ? k : remaining;
+  for (int i = 0; i < e; ++i) emitted[st->n_emitted + i] = st->cand[i];
+  st->n_emitted += e;
+  st->last_emitted = e;
+  st->last_m = st->last_k;
+  st->last_k = 0;
+  st->matched_steps += 1;
+  st->L += e;
+  *kv_L = st->L;
+  st->c0 = st->cand[e - 1];
+  for (int i = 0; i < k; ++i) st->cand[i] = st->c0;
+  jacobi_build(st, k);
+}
+
 // Cache relocation: the accepted verification rows of candidate last_k move from block rows
 // v(k, j) to cache rows L0 + j, j = 1..e-1, in every layer (L0 = cache length before the step).
 template <typename T>
@@ -324,5 +393,37 @@ extern "C" int la_ngram_accept(la_pool *p, la_kv *kv, const la_lookahead_desc *d
   }
   LA_HIP(hipGetLastError());
   kv->L_bound += d->N;
+  return LA_OK;
+}
+
+extern "C" int la_jacobi_init(la_kv *kv, int k, const int32_t *prompt, int P, int Bp, la_step_state *state, void *stream) {
+  LA_REQUIRE(kv && prompt && state, LA_EINVAL, "NULL argument");
+  LA_PENDING(kv->m);
+  LA_REQUIRE(k >= 1 && k <= Bp && Bp <= LA_MAX_ROWS, LA_EINVAL, "need 1 <= k=%d <= Bp=%d <= %d", k, Bp, LA_MAX_ROWS);
+  LA_REQUIRE(P >= 1, LA_EINVAL, "prompt must have at least one token");
+  LA_REQUIRE(P - 1 + Bp <= kv->max_len, LA_ERANGE, "prompt of %d tokens + block of %d rows exceeds max_len %d", P, Bp, kv->max_len);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps("jacobi_init", s);
+    jacobi_init_kernel<<<1, 64, 0, s>>>(state, prompt, P, k, Bp, kv->L_dev);
+  }
+  LA_HIP(hipGetLastError());
+  kv->L_bound = P - 1;
+  return LA_OK;
+}
+
+extern "C" int la_jacobi_accept(la_kv *kv, int k, const int32_t *ids, la_step_state *state, int32_t *emitted, int max_total,
+                                void *stream) {
+  LA_REQUIRE(kv && ids && state && emitted, LA_EINVAL, "NULL argument");
+  LA_PENDING(kv->m);
+  LA_REQUIRE(k >= 1 && k <= LA_MAX_ROWS, LA_EINVAL, "k=%d outside [1, %d]", k, LA_MAX_ROWS);
+  LA_REQUIRE(max_total >= 0, LA_EINVAL, "max_total < 0");
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps("jacobi_accept", s);
+    jacobi_accept_kernel<<<1, 64, 0, s>>>(state, ids, emitted, max_total, k, kv->L_dev, kv->err_dev);
+  }
+  LA_HIP(hipGetLastError());
+  kv->L_bound += k;
   return LA_OK;
 }

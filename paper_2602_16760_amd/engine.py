@@ -203,3 +203,33 @@ class Engine:
         return emitted.cpu().numpy().astype(np.int64), dict(
             steps=steps, tokens_per_step=n_new / steps, ms_per_step=wall / steps, local_ms=local / steps,
             cloud_ms=cloud / steps, tok_per_s=n_new / (wall / 1e3), matched_steps=st.matched_steps)
+
+    # -- Jacobi decoding (Section 4.2) ------------------------------------------------------------------
+    def generate_jacobi(self, prompt: np.ndarray, n_new: int, k: int, Bp: int | None = None, poll: int = 8):
+        """Greedy generation by Jacobi iteration on blocks of k positions.  Returns (tokens, stats):
+        passes (each one network round trip in the split deployment), blocks committed, tokens per pass."""
+        Bp = k if Bp is None else Bp
+        sh = self.shape
+        self.state = B.new_state()
+        self.prefill(np.asarray(prompt[:-1]))
+        B.la_jacobi_init(self.kv, k, B.to_device(np.asarray(prompt, dtype=np.int32)), Bp, self.state)
+        hidden = torch.empty((Bp, sh.d_model), dtype=torch.float32, device="cuda")
+        ids = torch.empty(Bp, dtype=torch.int32, device="cuda")
+        tok = B.state_field(self.state, "tok")[:Bp]
+        pos = B.state_field(self.state, "pos")[:Bp]
+        vis = B.state_field(self.state, "vis")[:Bp]
+        emitted = torch.zeros(n_new, dtype=torch.int32, device="cuda")
+        n_field = B.state_field(self.state, "n_emitted")
+        done = 0
+        while done < n_new:
+            for _ in range(poll):
+                B.la_embed(self.model, tok, hidden)
+                B.la_forward_layers(self.model, 0, sh.n_layers, hidden, pos, vis, self.kv)
+                B.la_unembed_argmax(self.model, hidden, ids)
+                B.la_jacobi_accept(self.kv, k, ids, self.state, emitted, n_new)
+            done = int(n_field.item())
+        st = B.read_state(self.state)
+        if st.error:
+            raise B.LaError(-4 if st.error & 4 else -3, f"a kernel raised error word {st.error} during generation")
+        return emitted.cpu().numpy().astype(np.int64), dict(passes=st.steps, blocks=st.matched_steps, n_emitted=st.n_emitted,
+                                                            L=st.L, tokens_per_pass=n_new / max(st.steps, 1))
