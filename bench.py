@@ -20,7 +20,8 @@ and never what `value` is quoted on): `config3` (24 layers, context 2048, 43-row
 48), `config4` (12B shape: 38 layers, hidden 5120, vocabulary 131072, context 4096, 32-row
 block), `config5` (all 32 layers of the 7B shape, 1024-token Markov prompt prefilled through
 the model, 512 tokens generated with lookahead and again one token at a time; `value` is then
-the emitted tokens per second of the lookahead run).
+the emitted tokens per second of the lookahead run), `split_sweep` (all 32 layers cut into a local head of
+2/4/6/8 layers, a cloud middle and a local tail of 2 layers + unembedding; local and cloud time per step).
 """
 from __future__ import annotations
 
@@ -324,6 +325,73 @@ def run_verify_steps(args):
     print(json.dumps(out), flush=True)
 
 
+def run_split_sweep(args):
+    """Section 5.2 / 5.3: how the step's time moves between the local and the cloud half as the number of local
+    layers grows (split after layer 1, 3, 5, 7: 2, 4, 6, 8 local layers at the input side; the last two layers,
+    the final norm and the unembedding stay local as in Section 4.1).  Each half is a layer range of
+    la_forward_layers; times are HIP-event times of the launches, for a one-row step and for the 32-row block."""
+    import torch
+    import synth
+    from paper_2602_16760_amd import binding as B
+
+    shape = synth.SHAPES["mistral7b"] if args.layers is None else synth.SHAPES["mistral7b"].with_layers(args.layers)
+    n, tail = shape.n_layers, 2
+    L_start = 512
+    eng = build_engine(shape, L_start + 256, kv_rows=L_start)
+    W, N, G, Bp = W_LA, N_LA, G_LA, BP
+    pos_h, vis_h = B.la_lookahead_layout(W, N, G, L_start, G, Bp)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        a, b = ev(), ev()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    rows = []
+    for rows_in_block in (1, Bp):
+        hidden = torch.zeros((rows_in_block, shape.d_model), dtype=torch.float32, device="cuda")
+        hidden.normal_(0.0, 1.0, generator=torch.Generator(device="cuda").manual_seed(0))
+        pos = B.to_device(pos_h[:rows_in_block].copy())
+        vis = B.to_device(vis_h[:rows_in_block].copy() if rows_in_block > 1 else np.array([1], dtype=np.uint64))
+        ids = torch.empty(rows_in_block, dtype=torch.int32, device="cuda")
+        for head_layers in (2, 4, 6, 8):
+            fwd = lambda lo, hi: B.la_forward_layers(eng.model, lo, hi, hidden, pos, vis, eng.kv)
+            t_head = timed(lambda: fwd(0, head_layers), args.steps)
+            t_cloud = timed(lambda: fwd(head_layers, n - tail), args.steps)
+            t_tail = timed(lambda: (fwd(n - tail, n), B.la_unembed_argmax(eng.model, hidden, ids)), args.steps)
+            hidden.normal_(0.0, 1.0)  # the residual stream grows over repeated passes: start each setting afresh
+            rows.append({"block_rows": rows_in_block, "local_layers": head_layers + tail, "split_after_layer": head_layers - 1,
+                         "local_ms": round(t_head + t_tail, 4), "cloud_ms": round(t_cloud, 4),
+                         "local_head_ms": round(t_head, 4), "local_tail_and_unembed_ms": round(t_tail, 4)})
+            log(json.dumps(rows[-1]))
+    per_layer = {}
+    for r in (1, Bp):
+        sel = [x for x in rows if x["block_rows"] == r]
+        per_layer[str(r)] = round((sel[-1]["local_head_ms"] - sel[0]["local_head_ms"]) / (sel[-1]["local_layers"] - sel[0]["local_layers"]), 4)
+    base = [x for x in rows if x["block_rows"] == Bp and x["local_layers"] == 4][0]
+    out = {
+        "metric": f"split-depth sweep, Mistral-7B shape, all {n} layers: local / cloud milliseconds per step (split_sweep)",
+        "value": per_layer[str(Bp)], "unit": "ms per additional local layer (32-row block)",
+        "n_gpus": 1, "steps": args.steps, "warmup": 3, "ms_per_step": round(base["local_ms"] + base["cloud_ms"], 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"Mistral-7B shape, {n} layers, KV prefilled to {L_start}; head layers 2/4/6/8 + {tail} tail layers local, "
+                               f"the rest cloud; one-row and {Bp}-row blocks; each half timed as its own launches",
+                   "name": "split_sweep", "arithmetic": ARITHMETIC},
+        "ms_per_additional_local_layer": per_layer,
+        "sweep": rows,
+        "paper_context": "Section 5.3: about 3 ms per additional local layer on the paper's local GPU (another machine: context only)",
+    }
+    eng.close()
+    print(json.dumps(out), flush=True)
+
+
 def run_generation(args):
     """BASELINE config 5: the prompt goes through the model, then 512 tokens are generated with
     the lookahead controller and again one token per step; both streams come from the same
@@ -419,7 +487,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["config5"], default="config2",
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["config5", "split_sweep"], default="config2",
                     help="config2 (default) is the configuration the metric is quoted on")
     ap.add_argument("--layers", type=int, default=None, help=argparse.SUPPRESS)
     ap.add_argument("--calib-copy", action="store_true",
@@ -437,6 +505,8 @@ def main():
         sys.exit(1)
     if args.workload == "config5":
         run_generation(args)
+    elif args.workload == "split_sweep":
+        run_split_sweep(args)
     else:
         run_verify_steps(args)
 
