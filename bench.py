@@ -392,6 +392,22 @@ def run_split_sweep(args):
     print(json.dumps(out), flush=True)
 
 
+def prefill_report(shape, n_tok, seconds):
+    """The prompt pass (la_prefill: 64-row causal chunks through the block kernel) against the matrix-core roofline:
+    2 flop per weight and token in the GEMMs plus the causal attention products."""
+    d, F, qd, kvd = shape.d_model, shape.d_ffn, shape.q_dim, shape.kv_dim
+    weights = shape.n_layers * (d * (qd + 2 * kvd) + qd * d + 3 * d * F)
+    attn = shape.n_layers * 2 * 2 * qd * n_tok * (n_tok + 1) / 2.0
+    flop = 2.0 * weights * n_tok + attn
+    chunks = (n_tok + 63) // 64
+    return {"tokens": n_tok, "seconds": round(seconds, 4), "tok_per_s": round(n_tok / seconds, 1), "flop": flop,
+            "tflop_per_s": round(flop / seconds / 1e12, 1), "frac_of_mfma_peak": round(flop / seconds / 2.5e15, 4),
+            "chunks": chunks, "ms_per_chunk": round(seconds * 1e3 / chunks, 3),
+            "note": "includes the controller set-up (pool seeding, first block) of la_state_init; each 64-row chunk streams "
+                    "every weight once, so the pass is bound by HBM, not by the matrix cores: a large-M design would stream "
+                    "them once per prompt"}
+
+
 def run_generation(args):
     """BASELINE config 5: the prompt goes through the model, then 512 tokens are generated with
     the lookahead controller and again one token per step; both streams come from the same
@@ -466,6 +482,7 @@ def run_generation(args):
         "sequential": {"steps": int(seq_st.steps), "seconds": round(seq_s, 4), "tok_per_s": round(n_new / seq_s, 1),
                        "ms_per_step": round(seq_s * 1e3 / seq_st.steps, 4), "prefill_seconds": round(seq_prefill_s, 4)},
         "speedup_over_sequential": round(seq_s / la_s, 3),
+        "prefill": prefill_report(shape, n_prompt - 1, la_prefill_s),
         "streams_equal_positions": same,
         "roofline": {
             "bound": "hbm", "kernel": dominant, "achieved": None, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": None,

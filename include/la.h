@@ -197,6 +197,15 @@ int la_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, fl
 int la_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                               void *stream);
 
+/* Prompt prefill (Section 4.1 step 1; Section 6.3 "Prefill"): runs the n tokens tok[0..n)
+ * (device int32) at positions L0.. through every layer, writes cache rows L0..L0+n-1 and
+ * sets L = L0 + n.  The prompt goes through the block kernel in causal chunks of LA_MAX_ROWS
+ * rows (the weights are streamed once per chunk), everything enqueued on `stream`; the hidden
+ * states are not returned (generation restarts from the last prompt token as c0).
+ * LA_ERANGE: L0 + n > max_len.  Chunked prefill is the paper's named future work (Section 8);
+ * a large-M design would run the prompt as one GEMM per matrix. */
+int la_prefill(la_model *m, la_kv *kv, const int32_t *tok, int n, int L0, void *stream);
+
 /* ---- n-gram pool and acceptance (Section 4.3) ----------------------------------------- */
 
 /* Pool keyed by token id: per key at most G distinct (N-1)-token continuations, refreshed

@@ -61,7 +61,7 @@ EXPORTS = [
     "la_init_model", "la_model_set_layer", "la_free_model", "la_kv_alloc", "la_kv_set_len", "la_kv_get_len",
     "la_kv_fill", "la_kv_read", "la_free_kv", "la_embed", "la_forward_layers", "la_unembed_argmax",
     "la_unembed_argmax_noalloc", "la_causal_layout", "la_set_barrier_timeout",
-    "la_jacobi_init", "la_jacobi_accept", "la_rtt_fixed_overhead", "la_rtt_project", "la_jacobi_project",
+    "la_prefill", "la_jacobi_init", "la_jacobi_accept", "la_rtt_fixed_overhead", "la_rtt_project", "la_jacobi_project",
     "la_pool_alloc", "la_free_pool", "la_state_init", "la_ngram_accept", "la_lookahead_layout",
     "la_profile_enable", "la_profile_select", "la_profile_read", "la_profile_copy", "la_last_error",
 ]
@@ -92,6 +92,7 @@ def _load():
         "la_free_pool": (None, [vp]),
         "la_state_init": (i32, [vp, vp, C.POINTER(la_lookahead_desc), vp, i32, i32, i32, vp, vp]),
         "la_ngram_accept": (i32, [vp, vp, C.POINTER(la_lookahead_desc), vp, vp, vp, i32, vp]),
+        "la_prefill": (i32, [vp, vp, vp, i32, i32, vp]),
         "la_jacobi_init": (i32, [vp, i32, vp, i32, i32, vp, vp]),
         "la_jacobi_accept": (i32, [vp, i32, vp, vp, vp, i32, vp]),
         "la_lookahead_layout": (i32, [C.POINTER(la_lookahead_desc), i32, i32, i32, C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]),
@@ -240,6 +241,11 @@ def la_state_init(pool, kv, W, N, G, prompt, Bp, seed_pool, state, stream=None):
 def la_ngram_accept(pool, kv, W, N, G, ids, state, emitted, max_total, stream=None):
     d = la_lookahead_desc(W, N, G)
     _check(lib.la_ngram_accept(pool, kv, C.byref(d), _ptr(ids), _ptr(state), _ptr(emitted), max_total, _stream(stream)))
+
+
+def la_prefill(model, kv, tok, L0=0, stream=None):
+    assert tok.dtype == torch.int32
+    _check(lib.la_prefill(model, kv, _ptr(tok), tok.shape[0], L0, _stream(stream)))
 
 
 def la_jacobi_init(kv, k, prompt, Bp, state, stream=None):

@@ -81,6 +81,15 @@ __global__ void kv_copy_kernel(T *Kl, T *Vl, T *k, T *v, int row0, int n, int Hk
 
 __global__ void set_i32_kernel(int32_t *p, int32_t v) { *p = v; }
 
+// positions t, t+1, ... and the plain causal masks of a chunk of n rows
+__global__ void causal_layout_kernel(int32_t *pos, uint64_t *vis, int t, int n) {
+  int i = threadIdx.x;
+  if (i < n) {
+    pos[i] = t + i;
+    vis[i] = i == 63 ? ~0ull : ((1ull << (i + 1)) - 1ull);
+  }
+}
+
 __global__ void calib_copy_kernel(uint4 *dst, const uint4 *src, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
 }
@@ -180,7 +189,8 @@ extern "C" void la_free_model(la_model *m) {
     for (void *p : ps)
       if (p) (void)hipFree(p);
   }
-  void *ps[] = {m->embed, m->unembed, m->g_final, m->h, m->qkv, m->attn, m->gu, m->act, m->logits, m->rope_cs, m->err_dev};
+  void *ps[] = {m->embed, m->unembed, m->g_final, m->h, m->qkv, m->attn, m->gu, m->act, m->logits, m->rope_cs, m->err_dev,
+                m->pf_hidden, m->pf_pos, m->pf_vis};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   if (m->err_host) (void)hipHostFree(m->err_host);
@@ -214,6 +224,8 @@ extern "C" int la_init_model(const la_model_desc *desc, const la_layer_weights *
   bool ok = true;
   ok = ok && (m->rope_cs = (float *)dev_alloc(R * d.head_dim * sizeof(float)));
   ok = ok && (m->err_dev = (int32_t *)dev_alloc(4)) && hipMemset(m->err_dev, 0, 4) == hipSuccess;
+  ok = ok && (m->pf_hidden = (float *)dev_alloc(R * d.d_model * 4));
+  ok = ok && (m->pf_pos = (int32_t *)dev_alloc(R * 4)) && (m->pf_vis = (uint64_t *)dev_alloc(R * 8));
   ok = ok && hipHostMalloc((void **)&m->err_host, 64, hipHostMallocMapped) == hipSuccess;
   if (ok) {
     memset(m->err_host, 0, 64);
@@ -513,4 +525,25 @@ extern "C" int la_jacobi_project(int k, double iterations, double rtt_ms, double
   LA_REQUIRE(k >= 1 && iterations > 0.0 && rtt_ms > 0.0, LA_EINVAL, "need k >= 1, iterations > 0 and rtt > 0");
   *tok_per_s = (double)k / (iterations * rtt_ms / 1000.0);
   return LA_OK;
+}
+
+extern "C" int la_prefill(la_model *m, la_kv *kv, const int32_t *tok, int n, int L0, void *stream) {
+  LA_REQUIRE(m && kv && (tok || n == 0), LA_EINVAL, "NULL argument");
+  LA_REQUIRE(kv->m == m, LA_EINVAL, "the cache belongs to another model");
+  LA_REQUIRE(m->embed != nullptr, LA_EINVAL, "model was created without an embedding table");
+  LA_REQUIRE(n >= 0 && L0 >= 0 && (long long)L0 + n <= kv->max_len, LA_ERANGE, "rows [%d, %d) outside the cache (max_len %d)", L0,
+             L0 + n, kv->max_len);
+  hipStream_t s = (hipStream_t)stream;
+  int rc = la_kv_set_len(kv, L0, stream);
+  for (int done = 0; !rc && done < n; done += LA_MAX_ROWS) {
+    const int rows = n - done < LA_MAX_ROWS ? n - done : LA_MAX_ROWS;
+    rc = la_embed(m, tok + done, rows, m->pf_hidden, stream);
+    if (rc) break;
+    causal_layout_kernel<<<1, 64, 0, s>>>(m->pf_pos, m->pf_vis, L0 + done, rows);
+    LA_HIP(hipGetLastError());
+    rc = la_forward_layers(m, 0, m->d.n_layers, m->pf_hidden, rows, m->pf_pos, m->pf_vis, kv, stream);
+    if (rc) break;
+    rc = la_kv_set_len(kv, L0 + done + rows, stream);
+  }
+  return rc;
 }

@@ -61,6 +61,10 @@ struct la_model {
   // scratch of the generic path, sized for LA_MAX_ROWS rows
   float *h = nullptr, *qkv = nullptr, *attn = nullptr, *gu = nullptr, *act = nullptr, *logits = nullptr;
   float *rope_cs = nullptr;  // [LA_MAX_ROWS][dh/2][2] cos, sin at each row's position
+  // la_prefill's chunk: residual stream [LA_MAX_ROWS, d], positions and causal masks of its rows
+  float *pf_hidden = nullptr;
+  int32_t *pf_pos = nullptr;
+  uint64_t *pf_vis = nullptr;
   la::MfmaModel *mf = nullptr;
   // Errors raised by kernels (a block that does not fit the cache: 1; a grid barrier that gave up: 4).  err_dev is the
   // device word the kernels OR into (the caches of this model alias it); err_host is one word of mapped pinned host

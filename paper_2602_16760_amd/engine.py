@@ -81,23 +81,12 @@ class Engine:
         return ids.cpu().numpy(), top2.cpu().numpy()
 
     # -- generation -------------------------------------------------------------------
-    def prefill(self, tokens: np.ndarray, L0: int = 0, chunk: int = 64):
-        """Runs tokens through all layers in causal chunks; cache rows L0.. are filled."""
-        sh = self.shape
-        L = L0
-        B.la_kv_set_len(self.kv, L)
+    def prefill(self, tokens: np.ndarray, L0: int = 0):
+        """Runs tokens through all layers (la_prefill: causal chunks inside the library); cache rows L0.. are filled."""
         toks = B.to_device(np.asarray(tokens, dtype=np.int32))
-        for s in range(0, len(tokens), chunk):
-            n = min(chunk, len(tokens) - s)
-            hidden = torch.empty((n, sh.d_model), dtype=torch.float32, device="cuda")
-            B.la_embed(self.model, toks[s:s + n].contiguous(), hidden)
-            pos_h, vis_h = B.la_causal_layout(L, n)
-            pos, vis = B.to_device(pos_h), B.to_device(vis_h)
-            B.la_forward_layers(self.model, 0, sh.n_layers, hidden, pos, vis, self.kv)
-            L += n
-            B.la_kv_set_len(self.kv, L)
+        B.la_prefill(self.model, self.kv, toks, L0)
         torch.cuda.synchronize()
-        return L
+        return L0 + len(tokens)
 
     def start(self, prompt: np.ndarray, W: int, N: int, G: int, Bp: int, seed_pool: bool = True,
               prefill: bool = True):
