@@ -182,6 +182,11 @@ ARITHMETIC = ("bf16 weights and KV cache; the weight GEMMs multiply the weights 
               "residual stream, norms, softmax f32")
 
 
+ARITHMETIC_F16 = ("f16 weights, embeddings and KV cache; the weight GEMMs multiply the weights as stored with activations rounded "
+                  "to f16 (values beyond +-65504 saturate) and f32 accumulation; attention on f16 MFMA; residual stream, norms, "
+                  "softmax f32")
+
+
 def run_verify_steps(args):
     """One block per step through the whole hot path, cache pre-filled with N(0, 1) rows."""
     import torch
@@ -192,6 +197,9 @@ def run_verify_steps(args):
     if args.layers is not None:
         n_layers = args.layers
     shape = synth.SHAPES[shape_name].with_layers(n_layers)
+    if args.storage == "f16":  # the paper's storage type (Section 6.1): weights, embeddings and cache as IEEE half
+        import dataclasses
+        shape = dataclasses.replace(shape, dtype="f16")
     rows = 1 + (W + G) * (N - 1)
     total_steps = args.warmup + args.steps + 8
     max_len = L_start + total_steps * N + Bp + 64
@@ -280,7 +288,7 @@ def run_verify_steps(args):
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": shape.dtype,
         "data": "synthetic",
         "config": {
             "workload": f"{what}, {n_layers} layers, KV prefilled to {L_start}, "
@@ -288,7 +296,7 @@ def run_verify_steps(args):
                         f"plus embedding gather, unembedding (vocab {shape.vocab}) + arg-max, n-gram accept + KV commit",
             "name": args.workload,
             "block_rows": Bp, "kv_len_start": int(st0.L), "kv_len_end": int(st1.L),
-            "arithmetic": ARITHMETIC,
+            "arithmetic": ARITHMETIC if shape.dtype == "bf16" else ARITHMETIC_F16,
         },
         "step_ms_quantiles": quantiles(step_ms),
         "step_hbm_gbps": round(gbps, 1),
@@ -507,6 +515,8 @@ def main():
     ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["config5", "split_sweep"], default="config2",
                     help="config2 (default) is the configuration the metric is quoted on")
     ap.add_argument("--layers", type=int, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--storage", choices=["bf16", "f16"], default="bf16",
+                    help="storage type of weights and cache for config2/3/4 (bf16 is what the metric is quoted on; f16 is the paper's)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch a 1 GiB copy kernel (calib_copy) before the timed steps: a dispatch of known "
                          "traffic for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings")

@@ -23,7 +23,10 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *    enqueue work and do not synchronise unless stated.
  *  - Matrices are row-major [in, out].  dtype LA_F32: weights and cache are float;
- *    LA_BF16: weights and cache are bfloat16 bit patterns.  The residual stream (`hidden`),
+ *    LA_BF16: weights and cache are bfloat16 bit patterns; LA_F16: weights, embedding table
+ *    and cache are IEEE half precision (the storage type of the paper's models, Section
+ *    6.1): the weight matrices are then multiplied exactly as stored and the attention
+ *    multiplies q, K, V and the probabilities in half precision instead of bfloat16.  The residual stream (`hidden`),
  *    norm gains, softmax and all accumulations are float in both cases.  In LA_BF16 the
  *    weight matrices are multiplied as IEEE half precision (a bfloat16 weight of magnitude
  *    2^-14 or more converts without loss, smaller ones to within 2^-25) with activations
@@ -68,7 +71,7 @@ typedef enum {
   LA_EHIP = -4    /* a HIP call failed, or a grid barrier gave up; la_last_error() has its text */
 } la_status;
 
-typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
+typedef enum { LA_F32 = 0, LA_BF16 = 1, LA_F16 = 2 } la_dtype;
 
 typedef struct la_model la_model; /* packed weights + per-model scratch */
 typedef struct la_kv la_kv;       /* K,V cache of all layers of one model + committed length */

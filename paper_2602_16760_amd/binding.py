@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblookahead.so")
 
 LA_MAX_ROWS = 64
-LA_F32, LA_BF16 = 0, 1
+LA_F32, LA_BF16, LA_F16 = 0, 1, 2
 
 
 class LaError(RuntimeError):
@@ -149,7 +149,7 @@ def to_device(a: np.ndarray) -> torch.Tensor:
 def make_desc(shape) -> la_model_desc:
     return la_model_desc(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                          shape.d_ffn, shape.vocab, shape.rms_eps, shape.rope_theta,
-                         LA_F32 if shape.dtype == "f32" else LA_BF16)
+                         {"f32": LA_F32, "bf16": LA_BF16, "f16": LA_F16}[shape.dtype])
 
 
 def _layer_struct(w: dict) -> la_layer_weights:

@@ -209,7 +209,7 @@ extern "C" int la_init_model(const la_model_desc *desc, const la_layer_weights *
   LA_REQUIRE(d.n_q_heads % d.n_kv_heads == 0, LA_EINVAL, "n_q_heads %d is not a multiple of n_kv_heads %d",
              d.n_q_heads, d.n_kv_heads);
   LA_REQUIRE(d.head_dim % 2 == 0 && d.head_dim <= 256, LA_EINVAL, "head_dim %d must be even and <= 256", d.head_dim);
-  LA_REQUIRE(d.dtype == LA_F32 || d.dtype == LA_BF16, LA_EINVAL, "unknown dtype %d", d.dtype);
+  LA_REQUIRE(d.dtype == LA_F32 || d.dtype == LA_BF16 || d.dtype == LA_F16, LA_EINVAL, "unknown dtype %d", d.dtype);
   LA_REQUIRE(d.rms_eps >= 0.f && d.rope_theta > 1.f, LA_EINVAL, "bad rms_eps / rope_theta");
   hipStream_t s = (hipStream_t)stream;
   la_model *m = new (std::nothrow) la_model();
@@ -219,7 +219,7 @@ extern "C" int la_init_model(const la_model_desc *desc, const la_layer_weights *
   (void)hipGetDevice(&m->device);
   m->layers.resize(d.n_layers);
   const char *force = getenv("LA_FORCE_GENERIC");
-  m->use_mfma = d.dtype == LA_BF16 && mfma_supported(&d) && !(force && force[0] == '1');
+  m->use_mfma = (d.dtype == LA_BF16 || d.dtype == LA_F16) && mfma_supported(&d) && !(force && force[0] == '1');
   size_t R = LA_MAX_ROWS;
   bool ok = true;
   ok = ok && (m->rope_cs = (float *)dev_alloc(R * d.head_dim * sizeof(float)));
@@ -430,6 +430,8 @@ extern "C" int la_embed(la_model *m, const int32_t *tok, int Bp, float *hidden, 
   ProfScope ps("embed", s);
   if (m->d.dtype == LA_F32)
     embed_kernel<float><<<Bp, 256, 0, s>>>((const float *)m->embed, tok, m->d.vocab, m->d.d_model, hidden);
+  else if (m->d.dtype == LA_F16)
+    embed_kernel<_Float16><<<Bp, 256, 0, s>>>((const _Float16 *)m->embed, tok, m->d.vocab, m->d.d_model, hidden);
   else
     embed_kernel<uint16_t><<<Bp, 256, 0, s>>>((const uint16_t *)m->embed, tok, m->d.vocab, m->d.d_model, hidden);
   LA_HIP(hipGetLastError());
@@ -478,7 +480,7 @@ extern "C" int la_unembed_argmax(la_model *m, const float *hidden, int Bp, int32
 extern "C" int la_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2, void *stream) {
   LA_REQUIRE(m && hidden && ids, LA_EINVAL, "NULL argument");
   LA_REQUIRE(Bp >= 1 && Bp <= LA_MAX_ROWS, LA_EINVAL, "Bp=%d outside [1, %d]", Bp, LA_MAX_ROWS);
-  LA_REQUIRE(m->use_mfma, LA_EINVAL, "only models on the matrix-core path (LA_BF16, supported shape) have this entry point");
+  LA_REQUIRE(m->use_mfma, LA_EINVAL, "only models on the matrix-core path (LA_BF16 or LA_F16, supported shape) have this entry point");
   LA_REQUIRE(m->g_final, LA_EINVAL, "model was created without final norm / unembedding");
   LA_PENDING(m);
   {

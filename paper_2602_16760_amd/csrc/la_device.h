@@ -18,7 +18,10 @@ template <typename T> __device__ __forceinline__ float load_as_float(const T *p)
 template <> __device__ __forceinline__ float load_as_float<float>(const float *p) { return *p; }
 template <> __device__ __forceinline__ float load_as_float<uint16_t>(const uint16_t *p) { return bf16_to_float(*p); }
 
+template <> __device__ __forceinline__ float load_as_float<_Float16>(const _Float16 *p) { return (float)*p; }
+
 template <typename T> __device__ __forceinline__ void store_from_float(T *p, float v);
+template <> __device__ __forceinline__ void store_from_float<_Float16>(_Float16 *p, float v) { *p = (_Float16)v; }
 template <> __device__ __forceinline__ void store_from_float<float>(float *p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_from_float<uint16_t>(uint16_t *p, float v) { *p = float_to_bf16(v); }
 

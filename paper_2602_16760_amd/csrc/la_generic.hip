@@ -297,6 +297,7 @@ static int forward_t(la_model *m, int lb, int le, float *hidden, int Bp, const i
 int generic_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32_t *pos, const uint64_t *vis,
                     la_kv *kv, hipStream_t s) {
   if (m->d.dtype == LA_F32) return forward_t<float>(m, lb, le, hidden, Bp, pos, vis, kv, s);
+  if (m->d.dtype == LA_F16) return forward_t<_Float16>(m, lb, le, hidden, Bp, pos, vis, kv, s);
   return forward_t<uint16_t>(m, lb, le, hidden, Bp, pos, vis, kv, s);
 }
 
@@ -309,6 +310,8 @@ int generic_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *id
   int rc;
   if (d.dtype == LA_F32)
     rc = gemm<float>("gemm_unembed", m->h, d.d_model, m->unembed, d.vocab, m->logits, d.vocab, Bp, d.d_model, d.vocab, 0, s);
+  else if (d.dtype == LA_F16)
+    rc = gemm<_Float16>("gemm_unembed", m->h, d.d_model, m->unembed, d.vocab, m->logits, d.vocab, Bp, d.d_model, d.vocab, 0, s);
   else
     rc = gemm<uint16_t>("gemm_unembed", m->h, d.d_model, m->unembed, d.vocab, m->logits, d.vocab, Bp, d.d_model, d.vocab, 0, s);
   if (rc) return rc;

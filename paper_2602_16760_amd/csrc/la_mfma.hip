@@ -41,6 +41,7 @@ struct PackSrc {
   const uint16_t *s0, *s1, *s2;
   int n0, n1, n2;
   int kind, F, dh;
+  int half;  // the source already is IEEE half (LA_F16): copied as stored
 };
 __device__ __forceinline__ const uint16_t *pack_col(const PackSrc &p, int pc, int &ld) {
   if (p.kind == 0) {
@@ -109,9 +110,10 @@ __global__ void pack_weights_kernel(PackSrc p, PackDst d) {
     uint16_t v[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float w = __uint_as_float((uint32_t)src[(size_t)(k0 + i) * ld] << 16);
+      const uint16_t bits = src[(size_t)(k0 + i) * ld];
+      const float w = __uint_as_float((uint32_t)bits << 16);
       const float lim = 65504.0f;
-      v[i] = __builtin_bit_cast(uint16_t, (_Float16)fminf(fmaxf(w, -lim), lim));
+      v[i] = p.half ? bits : __builtin_bit_cast(uint16_t, (_Float16)fminf(fmaxf(w, -lim), lim));
     }
     uint4 o;
     o.x = v[0] | ((uint32_t)v[1] << 16);
@@ -222,6 +224,7 @@ int mfma_create(la_model *m) {
   int cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
   f->n_wgs = std::max(1, std::min(env_int("LA_WGS", cus), cus));  // one resident workgroup per CU: the barrier needs co-residency
   f->use_r = env_int("LA_LDS_RING", 0) == 0;
+  LA_REQUIRE(f->use_r || d.dtype != LA_F16, LA_EINVAL, "LA_F16 models run on the register-streaming kernel only (unset LA_LDS_RING)");
   LA_REQUIRE((size_t)prop.sharedMemPerBlockOptin >= (size_t)LDS_BYTES || (size_t)prop.maxSharedMemoryPerMultiProcessor >= (size_t)LDS_BYTES,
              LA_EINVAL, "the device offers less LDS per workgroup than the %d bytes the kernel needs", LDS_BYTES);
   {  // co-residency of the grid: the barrier would otherwise wait for workgroups that cannot start
@@ -301,6 +304,7 @@ int mfma_set_layer(la_model *m, int layer, const la_layer_weights *w, hipStream_
       {(const uint16_t *)w->wdown, nullptr, nullptr, d.d_model, 0, 0, 0, 0, 0},
   };
   for (int gi = 0; gi < 4; ++gi) {
+    srcs[gi].half = d.dtype == LA_F16;
     PackDst dst{};
     dst.wstream = f->wstream;
     dst.cu_bytes = f->cu_bytes;
@@ -328,7 +332,7 @@ int mfma_set_head(la_model *m, const void *unembed, hipStream_t s) {
   if (!f->ustream) f->ustream = (uint8_t *)dalloc((size_t)f->n_wgs * f->ucu_bytes);
   LA_REQUIRE(f->ustream != nullptr, LA_ENOMEM, "device allocation of the unembedding stream failed");
   LA_HIP(hipMemsetAsync(f->ustream, 0, (size_t)f->n_wgs * f->ucu_bytes, s));
-  PackSrc u{(const uint16_t *)unembed, nullptr, nullptr, m->d.vocab, 0, 0, 0, 0, 0};
+  PackSrc u{(const uint16_t *)unembed, nullptr, nullptr, m->d.vocab, 0, 0, 0, 0, 0, m->d.dtype == LA_F16};
   PackDst dst{};
   dst.wstream = f->ustream;
   dst.cu_bytes = f->ucu_bytes;
@@ -582,6 +586,7 @@ int mfma_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32
   if (rc) return rc;
   StackArgs a = base_stack_args(m, Bp);
   a.mode = 0;
+  a.f16 = m->d.dtype == LA_F16;
   a.lb = lb;
   a.le = le;
   a.wstream = f->wstream;

@@ -749,8 +749,9 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
           y1[k] = x1;
         }
       }
-      u32x4 lo = {pack_bf16(y0[0], y0[1]), pack_bf16(y0[2], y0[3]), pack_bf16(y0[4], y0[5]), pack_bf16(y0[6], y0[7])};
-      u32x4 hi = {pack_bf16(y1[0], y1[1]), pack_bf16(y1[2], y1[3]), pack_bf16(y1[4], y1[5]), pack_bf16(y1[6], y1[7])};
+      const bool h16 = a.f16 != 0;
+      u32x4 lo = {pack_kv(h16, y0[0], y0[1]), pack_kv(h16, y0[2], y0[3]), pack_kv(h16, y0[4], y0[5]), pack_kv(h16, y0[6], y0[7])};
+      u32x4 hi = {pack_kv(h16, y1[0], y1[1]), pack_kv(h16, y1[2], y1[3]), pack_kv(h16, y1[4], y1[5]), pack_kv(h16, y1[6], y1[7])};
       const int o_lo = j, o_hi = (half >> 3) + j;
       if (hs < Hq) {
         __amdgpu_buffer_rsrc_t rqf = rsrc_of(a.qf);
@@ -768,8 +769,8 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
         int h = hs - Hq - Hkv;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          st16(rv, (unsigned)(v_index(true, L + b, h, 8 * j + k, Hkv, dh) * 2), float_to_bf16(y0[k]));
-          st16(rv, (unsigned)(v_index(true, L + b, h, half + 8 * j + k, Hkv, dh) * 2), float_to_bf16(y1[k]));
+          st16(rv, (unsigned)(v_index(true, L + b, h, 8 * j + k, Hkv, dh) * 2), kv_bits(h16, y0[k]));
+          st16(rv, (unsigned)(v_index(true, L + b, h, half + 8 * j + k, Hkv, dh) * 2), kv_bits(h16, y1[k]));
         }
       }
     }
@@ -989,10 +990,15 @@ __device__ __forceinline__ void r_kv_touch(const uint16_t *Kc, const uint16_t *V
 // waves of a unit's workgroup split the 32-key blocks, and wave 0 merges the others' partial
 // results in wave order.  The merge buffers sit in the MFMA waves' LDS regions, which are idle
 // between the QKV pass and the O pass.
-template <int DH, int MT, int NIO>
+template <int DH, int MT, int NIO, bool F16>
 __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const uint16_t *Kc, const uint16_t *Vc, uint16_t *attn_out, int L,
                                             int u0, unsigned &att_seq) {
   constexpr int KT = DH / 32, DT = DH / 16;
+  using v8 = std::conditional_t<F16, f16x8, bf16x8>;  // q, K, V and the probabilities: the cache's 16-bit type
+  auto mma = [](v8 x, v8 y, f32x4 c) {
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(x, y, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, c, 0, 0, 0);
+  };
   __amdgpu_buffer_rsrc_t rk = rsrc_of(Kc), rv = rsrc_of(Vc), rqf = rsrc_of(a.qf), ra = rsrc_of(attn_out);
   // per merging wave: DT KB of output tiles, then 512 B of (max, sum) per lane
   constexpr unsigned BUF = DT * 1024u + 512u;
@@ -1003,10 +1009,10 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
     const int kvh = u / n_rt, rt = u - kvh * n_rt;
     const int b = (rt % MT) * 16 + c16;
     const uint64_t vb = b < a.Bp ? a.vis[b] : 0ull;
-    bf16x8 q[KT];
+    v8 q[KT];
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt)
-      q[kt] = __builtin_bit_cast(bf16x8, ld128(rqf, (unsigned)(((((size_t)kvh * n_rt + rt) * KT + kt) * 64 + lane) * 16)));
+      q[kt] = __builtin_bit_cast(v8, ld128(rqf, (unsigned)(((((size_t)kvh * n_rt + rt) * KT + kt) * 64 + lane) * 16)));
     f32x4 o[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -1031,8 +1037,8 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
       f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int kt = 0; kt < KT; ++kt) {
-        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[kt]), q[kt], sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb2[kt]), q[kt], sb, 0, 0, 0);
+        sa = mma(__builtin_bit_cast(v8, ka[kt]), q[kt], sa);
+        sb = mma(__builtin_bit_cast(v8, kb2[kt]), q[kt], sb);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) sv[i] = i < 4 ? sa[i] : sb[i - 4];
@@ -1066,14 +1072,14 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
       ps += __shfl_xor(ps, 32, 64);
       l_run = l_run * corr + ps;
       m_run = m_new;
-      const u32x4 pw = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
-      return __builtin_bit_cast(bf16x8, pw);
+      const u32x4 pw = {pack_kv(F16, p[0], p[1]), pack_kv(F16, p[2], p[3]), pack_kv(F16, p[4], p[5]), pack_kv(F16, p[6], p[7])};
+      return __builtin_bit_cast(v8, pw);
     };
-    auto pv = [&](bf16x8 pb, float corr) {
+    auto pv = [&](v8 pb, float corr) {
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         o[dt] *= corr;
-        o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[dt]), pb, o[dt], 0, 0, 0);
+        o[dt] = mma(__builtin_bit_cast(v8, vt[dt]), pb, o[dt]);
       }
     };
     const std::integral_constant<int, 0> plain{};
@@ -1089,7 +1095,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
       load_k(coherent, kb, true);
       load_v(coherent, kb, true);
       scores(sv);
-      const bf16x8 pb = softmax(std::true_type{}, sv, kb, corr);
+      const v8 pb = softmax(std::true_type{}, sv, kb, corr);
       pv(pb, corr);
     }
     if (v < kb_split) {
@@ -1100,7 +1106,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
       for (;;) {
         scores(sv);
         load_k(plain, ne, ne < kb_split);
-        const bf16x8 pb = softmax(std::false_type{}, sv, kb, corr);
+        const v8 pb = softmax(std::false_type{}, sv, kb, corr);
         pv(pb, corr);
         load_v(plain, ne, ne < kb_split);
         if (ne >= kb_split) break;
@@ -1276,8 +1282,13 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
       set_phase(1 + 5 * (layer - a.lb) + (gemm <= 1 ? gemm : gemm + 1));
       if (gemm == 1) {
         if (att_u0 < n_units) {
-          const bool ok = a.dh == 128 ? r_attention<128, MT, NIO>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq)
-                                      : r_attention<64, MT, NIO>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq);
+          bool ok;
+          if (a.f16)
+            ok = a.dh == 128 ? r_attention<128, MT, NIO, true>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq)
+                             : r_attention<64, MT, NIO, true>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq);
+          else
+            ok = a.dh == 128 ? r_attention<128, MT, NIO, false>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq)
+                             : r_attention<64, MT, NIO, false>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq);
           if (!ok) return;
         }
         if (!io_grid_sync<NIO>(a, io, ++epoch)) return;

@@ -140,6 +140,7 @@ struct LayerGains {
 struct StackArgs {
   const LayerGains *gains;
   int mode;  // 0: layer stack, 1: unembedding
+  int f16;   // the cache, q and the attention's probabilities are IEEE half instead of bfloat16 (register-streaming kernel only)
   int dbg;   // timing experiments (results are wrong when set): 1 producer moves nothing, 2 one operand k-tile, 4 no operand loads, 8 no epilogue, 16 no K/V cache warming, 32 attention on the first workgroups, 64 every workgroup calls the attention, 128 x stays in memory
   int lb, le;
   int Bp, MT, d, Hq, Hkv, dh, F, ncg;
@@ -347,6 +348,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // largest finite value).  The weight GEMMs take their operands in this format: the bf16 weights
 // convert to it without loss (see pack_weights_kernel), and an activation keeps 11 significant
 // bits instead of 8, which removes most of the rounding noise of a deep stack.
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi);
+// two values in the cache's 16-bit type
+__device__ __forceinline__ uint32_t pack_kv(bool half, float lo, float hi) { return half ? pack_f16(lo, hi) : pack_bf16(lo, hi); }
+__device__ __forceinline__ uint16_t kv_bits(bool half, float v) { return (uint16_t)(pack_kv(half, v, 0.f) & 0xffffu); }
 __device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
   const float lim = 65504.0f;
   const _Float16 a = (_Float16)fminf(fmaxf(lo, -lim), lim), b = (_Float16)fminf(fmaxf(hi, -lim), lim);

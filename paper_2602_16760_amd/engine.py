@@ -52,13 +52,13 @@ class Engine:
 
     def read_kv(self, layer: int, row0: int, n: int):
         sh = self.shape
-        dt = torch.float32 if sh.dtype == "f32" else torch.int16
+        dt = {"f32": torch.float32, "bf16": torch.int16, "f16": torch.float16}[sh.dtype]
         k = torch.empty((n, sh.n_kv_heads, sh.head_dim), dtype=dt, device="cuda")
         v = torch.empty_like(k)
         B.la_kv_read(self.kv, layer, row0, n, k, v)
         torch.cuda.synchronize()
         k, v = k.cpu().numpy(), v.cpu().numpy()
-        if sh.dtype != "f32":
+        if sh.dtype == "bf16":
             k, v = k.view(np.uint16), v.view(np.uint16)
         return k, v
 

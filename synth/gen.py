@@ -33,7 +33,7 @@ class ModelShape:
     vocab: int
     rms_eps: float
     rope_theta: float
-    dtype: str  # "f32" or "bf16"
+    dtype: str  # "f32", "bf16" or "f16"
 
     def with_layers(self, n_layers: int) -> "ModelShape":
         return replace(self, n_layers=n_layers)
@@ -53,6 +53,9 @@ SHAPES = {
     # small bf16 shapes for parity tests: several tiles, ragged splits
     "small_bf16": ModelShape("small_bf16", 3, 512, 8, 2, 128, 1408, 2048, 1e-5, 1e6, "bf16"),
     "small64_bf16": ModelShape("small64_bf16", 2, 384, 6, 2, 64, 1056, 1536, 1e-5, 1e4, "bf16"),
+    # the same two shapes stored as IEEE half (the paper's own storage type, Section 6.1)
+    "small_f16": ModelShape("small_f16", 3, 512, 8, 2, 128, 1408, 2048, 1e-5, 1e6, "f16"),
+    "small64_f16": ModelShape("small64_f16", 2, 384, 6, 2, 64, 1056, 1536, 1e-5, 1e4, "f16"),
     # Mistral-7B shape (32 layers in full; tests and bench pick a layer count)
     "mistral7b": ModelShape("mistral7b", 32, 4096, 32, 8, 128, 14336, 32768, 1e-5, 1e6, "bf16"),
     # Mistral-NeMo-12B shape
@@ -77,10 +80,12 @@ def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
 
 
 def normal(seed: int, name: str, shape, std: float = 1.0, dtype: str = "f32") -> np.ndarray:
-    """N(0, std) tensor.  dtype "f32" -> float32 array; "bf16" -> uint16 bits."""
+    """N(0, std) tensor.  dtype "f32" -> float32 array; "bf16" -> uint16 bits; "f16" -> float16 array."""
     x = _rng(seed, name).standard_normal(shape, dtype=np.float32)
     if std != 1.0:
         x *= np.float32(std)
+    if dtype == "f16":
+        return x.astype(np.float16)
     return bf16_bits(x) if dtype == "bf16" else x
 
 

@@ -15,7 +15,7 @@ from tests.gpu_util import gpu_engine, oracle_model, prefill_both, row_rel_err
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
+TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 1e-3}   # (a half-precision cache keeps 11 significant bits where bfloat16 keeps 8)
 MARGIN = 1e-2
 
 
@@ -40,6 +40,10 @@ CASES = [
     ("small_bf16", 2, 0, (5, 4, 5), 32, 0),       # empty cache on the matrix-core path: only this step's rows are keys
     ("small_bf16", 2, 96, (10, 4, 11), 64, 11),   # the largest block (64 rows, four row tiles), cache a whole number of key blocks
     ("small64_bf16", 1, 1, (3, 2, 2), 6, 1),      # one cached row
+    # the fp16-storage variant (Section 6.1: the paper's models are float16): weights and cache IEEE half
+    ("small_f16", 3, 100, (5, 4, 5), 32, 3),
+    ("small_f16", 2, 515, (7, 4, 7), 48, 7),
+    ("small64_f16", 2, 77, (4, 3, 4), 17, 4),
 ]
 
 
@@ -98,7 +102,7 @@ def test_layer_ranges_compose(name):
         eng.close()
 
 
-@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16", "small64_bf16"])
+@pytest.mark.parametrize("name", ["tiny_f32", "small_bf16", "small64_bf16", "small_f16"])
 def test_rows_do_not_depend_on_block_size(name):
     """A row's result depends on what it sees, not on how many other rows ride along:
     row 0 of a lookahead block equals the one-row sequential step (Section 4.2/6.5)."""
@@ -117,7 +121,7 @@ def test_rows_do_not_depend_on_block_size(name):
         eng.close()
 
 
-@pytest.mark.parametrize("name,Bp", [("tiny_f32", 17), ("small_bf16", 32), ("small64_bf16", 48)])
+@pytest.mark.parametrize("name,Bp", [("tiny_f32", 17), ("small_bf16", 32), ("small64_bf16", 48), ("small_f16", 32)])
 def test_unembed_argmax_matches_oracle(name, Bp):
     shape = synth.SHAPES[name].with_layers(1)
     om = oracle_model(shape, seed=7)
@@ -422,7 +426,7 @@ def _orbit_model(shape, period, seed):
     return perm, layer, head
 
 
-@pytest.mark.parametrize("name", ["small_bf16", "small64_bf16"])
+@pytest.mark.parametrize("name", ["small_bf16", "small64_bf16", "small_f16"])
 def test_closed_form_periodic_text_reaches_n_tokens_per_step(name):
     """Acceptance on the matrix-core path, with the expected stream known without any forward
     pass: lookahead = sequential = the orbit of perm, N tokens per step once the pool knows the
@@ -559,11 +563,12 @@ def test_teacher_forced_steps_over_relocated_rows(name, Bp):
         eng.close()
 
 
-def test_ragged_workgroup_count_and_plain_kernels_agree(monkeypatch):
-    """The same block through three builds of the same bf16 model: all workgroups (the default),
+@pytest.mark.parametrize("name", ["small_bf16", "small_f16"])
+def test_ragged_workgroup_count_and_plain_kernels_agree(monkeypatch, name):
+    """The same block through three builds of the same 16-bit model: all workgroups (the default),
     a workgroup count that leaves every matrix with a ragged tile split (LA_WGS), and the plain
     tiled kernels (LA_FORCE_GENERIC): each within the bar of the oracle."""
-    shape = synth.SHAPES["small_bf16"].with_layers(2)
+    shape = synth.SHAPES[name].with_layers(2)
     L, Bp = 45, 32
     om = oracle_model(shape, seed=3, head=False)
     okv = otf.KVCache(shape, L + Bp)
@@ -580,7 +585,7 @@ def test_ragged_workgroup_count_and_plain_kernels_agree(monkeypatch):
             prefill_both(shape, eng, otf.KVCache(shape, L + Bp), L, seed=4)
             err = row_rel_err(eng.forward(x, pos, vis), want)
             print(env, f"max row rel err {err.max():.3e}")
-            assert err.max() <= TOL["bf16"]
+            assert err.max() <= TOL[shape.dtype]
         finally:
             eng.close()
             for k in env:
