@@ -152,6 +152,8 @@ struct MfmaModel {
   float *rsq = nullptr, *rsq_u = nullptr;
   Top *un_part = nullptr;
   int un_parts_per_cu = 0;
+  float *att_part = nullptr;    // attention with the keys split over workgroups: one partial record per workgroup
+  unsigned *att_cnt = nullptr;  // ... and per unit the number of records delivered
   unsigned *sync = nullptr;
   int32_t *zero_len = nullptr;  // a cache length of 0: the unembedding has no cache to overflow
   unsigned epoch = 0;
@@ -195,7 +197,7 @@ void mfma_destroy(la_model *m) {
   MfmaModel *f = m->mf;
   if (!f) return;
   void *ps[] = {f->wstream, f->ustream, f->xa, f->attn_a, f->act_a, f->qf, f->xa_u, f->rsq_u, f->rsq, f->un_part,
-                f->sync, f->dev_gains, f->zero_len, f->trace};
+                f->sync, f->dev_gains, f->zero_len, f->trace, f->att_part, f->att_cnt};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   delete f;
@@ -264,6 +266,8 @@ int mfma_create(la_model *m) {
   ok = ok && (f->sync = (unsigned *)dalloc((size_t)n_sync * 4));
   ok = ok && (f->dev_gains = (LayerGains *)dalloc((size_t)d.n_layers * sizeof(LayerGains)));
   ok = ok && (f->zero_len = (int32_t *)dalloc(8));
+  ok = ok && (f->att_part = (float *)dalloc((size_t)f->n_wgs * (8 * 1024 + 512)));
+  ok = ok && (f->att_cnt = (unsigned *)dalloc((size_t)d.n_q_heads * MAX_MT * 4));
   LA_REQUIRE(ok, LA_ENOMEM, "device allocation failed in the MFMA path");
   LA_HIP(hipMemset(f->wstream, 0, (size_t)f->n_wgs * f->cu_bytes));  // padding fragments are streamed too
   // pad rows of the operand buffers are read by the MFMAs: keep them finite
@@ -563,6 +567,8 @@ static StackArgs base_stack_args(la_model *m, int Bp) {
   a.rsq = f->rsq;
   a.cs = m->rope_cs;
   a.sync = f->sync;
+  a.att_part = f->att_part;
+  a.att_cnt = f->att_cnt;
   a.err = m->err_dev;
   a.err_map = m->err_map;
   a.spin_global = m->barrier_spins ? m->barrier_spins : SPIN_GLOBAL;

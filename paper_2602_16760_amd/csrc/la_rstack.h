@@ -992,7 +992,7 @@ __device__ __forceinline__ void r_kv_touch(const uint16_t *Kc, const uint16_t *V
 // between the QKV pass and the O pass.
 template <int DH, int MT, int NIO, bool F16>
 __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const uint16_t *Kc, const uint16_t *Vc, uint16_t *attn_out, int L,
-                                            int u0, unsigned &att_seq) {
+                                            int su0, int S, unsigned &att_seq) {
   constexpr int KT = DH / 32, DT = DH / 16;
   using v8 = std::conditional_t<F16, f16x8, bf16x8>;  // q, K, V and the probabilities: the cache's 16-bit type
   auto mma = [](v8 x, v8 y, f32x4 c) {
@@ -1005,8 +1005,17 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
   const int v = io.v, lane = io.lane, q4 = lane >> 4, c16 = lane & 15;
   const int g = a.Hq / a.Hkv, n_rt = g * MT;
   const int total = L + a.Bp, nkb = (total + 31) >> 5;
-  for (int u = u0; u < a.Hkv * n_rt; u += gridDim.x) {
-    const int kvh = u / n_rt, rt = u - kvh * n_rt;
+  // Split units: unit u = su % n_units, key slice ks = su / n_units of S.  With S > 1 the committed key blocks are cut
+  // into S contiguous runs (the blocks holding this step's rows go with the last run); every split unit leaves its
+  // (o, m, l) in memory, and the one that delivers last adds all S records in slice order and writes the result, so the
+  // sum has one order whoever forms it.
+  const int n_units = a.Hkv * n_rt;
+  constexpr unsigned PART = DT * 1024u + 512u;  // bytes of a record: DT output tiles (16 B per lane each), then (m, l) per lane
+  for (int su = su0; su < n_units * S; su += gridDim.x) {
+    const int u = su % n_units, ks = su / n_units;
+    // unit u = kvh + Hkv * rt sits on workgroup att_first + u: with 8 kv heads (and the first unit on a multiple of 8)
+    // all units of a kv head run on one XCD and share its K, V lines in that XCD's L2 (r_kv_touch warms exactly those)
+    const int rt = u / a.Hkv, kvh = u - rt * a.Hkv;
     const int b = (rt % MT) * 16 + c16;
     const uint64_t vb = b < a.Bp ? a.vis[b] : 0ull;
     v8 q[KT];
@@ -1085,12 +1094,13 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
     const std::integral_constant<int, 0> plain{};
     const std::integral_constant<int, DEV> coherent{};
     const int kb_split = L >> 5;  // key blocks 0 .. kb_split - 1 end at or before row L ("early")
+    const int e_lo = kb_split * ks / S, e_hi = kb_split * (ks + 1) / S;  // this slice's early blocks
     // The blocks that hold rows of this step ("late": at most three, written by other workgroups in
     // the phase before, so device-scope loads and the mask) are dealt to the waves round-robin and
     // taken first, one at a time; the early blocks (ordinary loads, every key visible) follow in
     // the wave's pipeline: the next block's K is requested as soon as the scores are out of the
     // matrix unit, the next V after P V.
-    for (int kb = kb_split + v; kb < nkb; kb += NIO) {
+    for (int kb = kb_split + v; kb < nkb && ks == S - 1; kb += NIO) {
       float sv[8], corr;
       load_k(coherent, kb, true);
       load_v(coherent, kb, true);
@@ -1098,18 +1108,18 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
       const v8 pb = softmax(std::true_type{}, sv, kb, corr);
       pv(pb, corr);
     }
-    if (v < kb_split) {
-      int kb = v, ne = v + NIO;
+    if (e_lo + v < e_hi) {
+      int kb = e_lo + v, ne = kb + NIO;
       float sv[8], corr;
       load_k(plain, kb, true);
       load_v(plain, kb, true);
       for (;;) {
         scores(sv);
-        load_k(plain, ne, ne < kb_split);
+        load_k(plain, ne, ne < e_hi);
         const v8 pb = softmax(std::false_type{}, sv, kb, corr);
         pv(pb, corr);
-        load_v(plain, ne, ne < kb_split);
-        if (ne >= kb_split) break;
+        load_v(plain, ne, ne < e_hi);
+        if (ne >= e_hi) break;
         kb = ne;
         ne += NIO;
       }
@@ -1139,7 +1149,40 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
         for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * ca + red[dt * 64 + lane] * cb;
         m_run = m_new;
       }
-      if (b < a.Bp) {
+      bool writer = true;
+      if (S > 1) {
+        __amdgpu_buffer_rsrc_t rp = rsrc_of(a.att_part);
+        const unsigned mine = (unsigned)su * PART;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) st128(rp, mine + (unsigned)(dt * 64 + lane) * 16u, __builtin_bit_cast(u32x4, o[dt]));
+        st64(rp, mine + DT * 1024u + (unsigned)lane * 8u, u32x2{__float_as_uint(m_run), __float_as_uint(l_run)});
+        wait_vmcnt<0>();  // the record is acknowledged before it is counted
+        unsigned last = 0;
+        if (lane == 0) {
+          const unsigned old = __hip_atomic_fetch_add(a.att_cnt + u, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          last = ((old + 1u) % (unsigned)S) == 0u ? 1u : 0u;
+        }
+        writer = uni(last) != 0u;
+        if (writer) {
+          m_run = -1e30f;
+          l_run = 0.f;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          for (int k = 0; k < S; ++k) {
+            const unsigned rec = (unsigned)(u + n_units * k) * PART;
+            const u32x2 ml2 = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rp, rec + DT * 1024u + (unsigned)lane * 8u, 0, DEV));
+            const float mo = __uint_as_float(ml2[0]), lo = __uint_as_float(ml2[1]);
+            const float m_new = fmaxf(m_run, mo);
+            const float ca = __expf(m_run - m_new), cb = __expf(mo - m_new);
+            l_run = l_run * ca + lo * cb;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+              o[dt] = o[dt] * ca + __builtin_bit_cast(f32x4, ld128(rp, rec + (unsigned)(dt * 64 + lane) * 16u)) * cb;
+            m_run = m_new;
+          }
+        }
+      }
+      if (writer && b < a.Bp) {
         const float inv = 1.0f / l_run;
         const int j = rt / MT;
 #pragma unroll
@@ -1266,8 +1309,18 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
   const int nt_x = pw.tiles_of(1);
   const int x_lds = (nt_x * MT * 1024 <= X_BYTES && nt_x <= 4) ? 1 : 0;  // (one load instruction stages the gains of four tiles)
   const int n_rt = a.Hq / a.Hkv * MT, n_units = a.Hkv * n_rt;
-  const int att_first = att_first_wg(a.qkv.ntiles, n_units);
-  const int att_u0 = (int)blockIdx.x >= att_first ? (int)blockIdx.x - att_first : n_units;
+  // Key split of the attention: S slices per unit while every split unit still gets a workgroup of its own and a wave
+  // keeps four or more key blocks (short contexts gain nothing from more workgroups: the merge costs what they save).
+  int S = 1;
+  {
+    const int nkb = (L + a.Bp + 31) >> 5;
+    while (S < 8 && n_units * 2 * S <= (int)gridDim.x && nkb >= 16 * 2 * S) S *= 2;
+  }
+  const int n_su = n_units * S;
+  const int att_first = att_first_wg(a.qkv.ntiles, n_su);
+  const int att_u0 = (int)blockIdx.x >= att_first ? (int)blockIdx.x - att_first : n_su;
+  if (blockIdx.x == 0)  // the delivery counters start every launch at zero (visible after the first grid barrier)
+    for (int i = io.tid; i < n_units; i += NIO * 64) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc_of(a.att_cnt), (unsigned)i * 4u, 0, DEV);
   r_prep<NIO>(a, io, a.gains[a.lb].g_attn, a.xa + (size_t)(2 * a.lb) * a.xa_stride, a.rsq + (size_t)(2 * a.lb) * a.rsq_stride);
   r_rope_table<NIO>(a, io);
   if (x_lds) r_x_stage<MT, NIO>(a, io, nt_x);
@@ -1281,14 +1334,14 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
       if (!io_grid_sync<NIO>(a, io, ++epoch)) return;
       set_phase(1 + 5 * (layer - a.lb) + (gemm <= 1 ? gemm : gemm + 1));
       if (gemm == 1) {
-        if (att_u0 < n_units) {
+        if (att_u0 < n_su) {
           bool ok;
           if (a.f16)
-            ok = a.dh == 128 ? r_attention<128, MT, NIO, true>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq)
-                             : r_attention<64, MT, NIO, true>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq);
+            ok = a.dh == 128 ? r_attention<128, MT, NIO, true>(a, io, Kc, Vc, attn_l, L, att_u0, S, att_seq)
+                             : r_attention<64, MT, NIO, true>(a, io, Kc, Vc, attn_l, L, att_u0, S, att_seq);
           else
-            ok = a.dh == 128 ? r_attention<128, MT, NIO, false>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq)
-                             : r_attention<64, MT, NIO, false>(a, io, Kc, Vc, attn_l, L, att_u0, att_seq);
+            ok = a.dh == 128 ? r_attention<128, MT, NIO, false>(a, io, Kc, Vc, attn_l, L, att_u0, S, att_seq)
+                             : r_attention<64, MT, NIO, false>(a, io, Kc, Vc, attn_l, L, att_u0, S, att_seq);
           if (!ok) return;
         }
         if (!io_grid_sync<NIO>(a, io, ++epoch)) return;
@@ -1326,7 +1379,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
         pw.next();
       }
       if (gemm == 0)
-        for (int u = att_u0; u < n_units; u += gridDim.x) r_kv_touch<NIO>(Kc, Vc, u, n_rt, a.Hkv, a.dh, L, io);
+        for (int u = att_u0; u < n_units; u += gridDim.x) r_kv_touch<NIO>(Kc, Vc, u, n_rt, a.Hkv, a.dh, L, io);  // (the first slice's workgroups)
     }
   }
   io_mark(io, 2);

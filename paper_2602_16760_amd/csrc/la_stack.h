@@ -169,6 +169,10 @@ struct StackArgs {
   int32_t *err;      // device error word: 1 the block does not fit the cache, 4 a grid barrier gave up
   int32_t *err_map;  // mapped host word that receives the same code (plain store), read by the host without synchronising
   unsigned spin_global;  // polls of the barrier's release word before a workgroup gives up
+  // attention with the keys split over workgroups (register-streaming kernel): partial (o, m, l) records per
+  // split unit, and per unit a counter of the records delivered
+  float *att_part;
+  unsigned *att_cnt;
   const float *g_final;
   Top *un_part;
   int un_parts_per_cu;

@@ -44,6 +44,10 @@ CASES = [
     ("small_f16", 3, 100, (5, 4, 5), 32, 3),
     ("small_f16", 2, 515, (7, 4, 7), 48, 7),
     ("small64_f16", 2, 77, (4, 3, 4), 17, 4),
+    # long contexts: the attention's keys are split over workgroups (two, four slices) and merged by the last to deliver
+    ("small_bf16", 2, 1100, (5, 4, 5), 32, 3),
+    ("small64_bf16", 1, 2300, (7, 4, 7), 48, 7),
+    ("small_f16", 1, 2101, (4, 3, 4), 17, 2),
 ]
 
 
