@@ -401,19 +401,16 @@ def run_split_sweep(args):
 
 
 def prefill_report(shape, n_tok, seconds):
-    """The prompt pass (la_prefill: 64-row causal chunks through the block kernel) against the matrix-core roofline:
-    2 flop per weight and token in the GEMMs plus the causal attention products."""
+    """The prompt pass (la_prefill: one matrix product per weight matrix and 1024-token chunk, causal attention over
+    the cache) against the matrix-core roofline: 2 flop per weight and token in the GEMMs plus the attention products."""
     d, F, qd, kvd = shape.d_model, shape.d_ffn, shape.q_dim, shape.kv_dim
     weights = shape.n_layers * (d * (qd + 2 * kvd) + qd * d + 3 * d * F)
     attn = shape.n_layers * 2 * 2 * qd * n_tok * (n_tok + 1) / 2.0
     flop = 2.0 * weights * n_tok + attn
-    chunks = (n_tok + 63) // 64
     return {"tokens": n_tok, "seconds": round(seconds, 4), "tok_per_s": round(n_tok / seconds, 1), "flop": flop,
             "tflop_per_s": round(flop / seconds / 1e12, 1), "frac_of_mfma_peak": round(flop / seconds / 2.5e15, 4),
-            "chunks": chunks, "ms_per_chunk": round(seconds * 1e3 / chunks, 3),
-            "note": "includes the controller set-up (pool seeding, first block) of la_state_init; each 64-row chunk streams "
-                    "every weight once, so the pass is bound by HBM, not by the matrix cores: a large-M design would stream "
-                    "them once per prompt"}
+            "note": "wall time of Engine.start: the large-M prompt pass plus the controller set-up (pool seeding, first block) "
+                    "of la_state_init; peak = 2.5 PFLOP/s dense f16"}
 
 
 def run_generation(args):
@@ -480,7 +477,7 @@ def run_generation(args):
         "data": "synthetic",
         "config": {
             "workload": f"Mistral-7B shape, {shape.n_layers} layers + embedding + unembedding (vocab {shape.vocab}); {n_prompt}-token "
-                        f"Markov prompt (40 % repeated spans) prefilled through the model in 64-row chunks; {n_new} tokens "
+                        f"Markov prompt (40 % repeated spans) prefilled through the model by la_prefill (large-M pass); {n_new} tokens "
                         f"generated with W={W}, N={N}, G={G} ({Bp}-row block) and again one token per step",
             "name": "config5", "block_rows": Bp, "arithmetic": ARITHMETIC,
         },
@@ -495,7 +492,7 @@ def run_generation(args):
         "roofline": {
             "bound": "hbm", "kernel": dominant, "achieved": None, "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": None,
             "traffic": None, "bytes_per_launch": dom_bytes, "launches": launches,
-            "note": f"the {launches} launches include {n_prefill_launches} prefill launches of 64 rows",
+            "note": f"{launches} launches of the lookahead run (the prompt pass has kernels of its own)",
         },
     }
     if launches:

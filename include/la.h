@@ -202,11 +202,14 @@ int la_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t 
 
 /* Prompt prefill (Section 4.1 step 1; Section 6.3 "Prefill"): runs the n tokens tok[0..n)
  * (device int32) at positions L0.. through every layer, writes cache rows L0..L0+n-1 and
- * sets L = L0 + n.  The prompt goes through the block kernel in causal chunks of LA_MAX_ROWS
- * rows (the weights are streamed once per chunk), everything enqueued on `stream`; the hidden
- * states are not returned (generation restarts from the last prompt token as c0).
- * LA_ERANGE: L0 + n > max_len.  Chunked prefill is the paper's named future work (Section 8);
- * a large-M design would run the prompt as one GEMM per matrix. */
+ * sets L = L0 + n.  Prompts of 128 tokens or more on the matrix-core path run as one matrix
+ * product per weight matrix and chunk of 1024 tokens (the weights are read once per chunk),
+ * with a causal attention kernel over the cache; shorter prompts, and models on the plain
+ * kernels, go through the block kernel in causal chunks of LA_MAX_ROWS rows.  Everything is
+ * enqueued on `stream`; the hidden states are not returned (generation restarts from the last
+ * prompt token as c0).  The first large prompt on a model allocates its buffers (about
+ * 1024 x (d_model x 8 + d_ffn x 2 + Hq x dh x 4) bytes).  LA_ERANGE: L0 + n > max_len.
+ * (Chunked prefill is the paper's named future work, Section 8.) */
 int la_prefill(la_model *m, la_kv *kv, const int32_t *tok, int n, int L0, void *stream);
 
 /* ---- n-gram pool and acceptance (Section 4.3) ----------------------------------------- */

@@ -537,6 +537,18 @@ extern "C" int la_prefill(la_model *m, la_kv *kv, const int32_t *tok, int n, int
              L0 + n, kv->max_len);
   hipStream_t s = (hipStream_t)stream;
   int rc = la_kv_set_len(kv, L0, stream);
+  if (!rc && m->use_mfma && mfma_prefill_rows(m) > 0 && n >= mfma_prefill_min()) {
+    // the large-M pass: one matrix product per weight matrix and prompt chunk
+    for (int l = 0; l < m->d.n_layers; ++l) LA_REQUIRE(m->layers[l].set, LA_EINVAL, "layer %d has no weights", l);
+    if ((rc = recover_if_needed(m, s))) return rc;
+    const int rows = mfma_prefill_rows(m);
+    for (int done = 0; !rc && done < n; done += rows) {
+      const int M = n - done < rows ? n - done : rows;
+      rc = mfma_prefill_chunk(m, kv, tok + done, M, L0 + done, s);
+      if (!rc) rc = la_kv_set_len(kv, L0 + done + M, stream);
+    }
+    return rc;
+  }
   for (int done = 0; !rc && done < n; done += LA_MAX_ROWS) {
     const int rows = n - done < LA_MAX_ROWS ? n - done : LA_MAX_ROWS;
     rc = la_embed(m, tok + done, rows, m->pf_hidden, stream);

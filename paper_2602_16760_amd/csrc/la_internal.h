@@ -129,6 +129,9 @@ int mfma_forward(la_model *m, int lb, int le, float *hidden, int Bp, const int32
 int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                         hipStream_t s);
 void mfma_reset_sync(la_model *m, hipStream_t s);
+int mfma_prefill_rows(const la_model *m);  // rows of one large-M prompt chunk; 0: this model has no large-M path
+int mfma_prefill_min();                    // prompts shorter than this go through the block kernel
+int mfma_prefill_chunk(la_model *m, la_kv *kv, const int32_t *tok, int M, int L0, hipStream_t s);
 int mfma_unembed_argmax_noalloc(la_model *m, const float *hidden, int Bp, int32_t *ids, float *top2,
                                 hipStream_t s);
 }  // namespace la

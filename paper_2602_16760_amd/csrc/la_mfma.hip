@@ -135,6 +135,11 @@ struct GemmPlan {
   int N = 0, K = 0, KT = 0, ntiles = 0, ntp = 1, nt_max = 0;
 };
 
+struct PfBuffers {  // the large-M prompt pass (la_prefill.h), allocated at its first use
+  float *x = nullptr, *rs = nullptr, *cs = nullptr;
+  uint16_t *A = nullptr, *Q = nullptr, *attn = nullptr, *act = nullptr;
+};
+
 struct MfmaModel {
   int n_wgs = 256;
   bool use_r = true;  // the register-streaming kernel (la_rstack.h); false: the LDS-ring kernel (la_stack.h)
@@ -159,6 +164,7 @@ struct MfmaModel {
   unsigned epoch = 0;
   unsigned long long *trace = nullptr;  // LA_TRACE=1: per-phase timestamps, printed after each launch
   int trace_phases = 0;
+  PfBuffers pf;
 };
 
 static int env_int(const char *name, int dflt) {
@@ -197,7 +203,8 @@ void mfma_destroy(la_model *m) {
   MfmaModel *f = m->mf;
   if (!f) return;
   void *ps[] = {f->wstream, f->ustream, f->xa, f->attn_a, f->act_a, f->qf, f->xa_u, f->rsq_u, f->rsq, f->un_part,
-                f->sync, f->dev_gains, f->zero_len, f->trace, f->att_part, f->att_cnt};
+                f->sync, f->dev_gains, f->zero_len, f->trace, f->att_part, f->att_cnt,
+                f->pf.x, f->pf.rs, f->pf.cs, f->pf.A, f->pf.Q, f->pf.attn, f->pf.act};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   delete f;
@@ -629,6 +636,10 @@ int mfma_unembed_argmax(la_model *m, const float *hidden, int Bp, int32_t *ids, 
   a.max_len = LA_MAX_ROWS;
   return launch_stack("unembed_argmax", f, a, 2, s);
 }
+
+}  // namespace la
+#include "la_prefill.h"
+namespace la {
 
 // ---- the unembedding for callers that cannot allocate ------------------------------------------------
 // Everything the unembedding kernel needs beyond the caller's buffers and the packed weights sits in one static array per
