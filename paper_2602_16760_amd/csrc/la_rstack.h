@@ -1411,6 +1411,7 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
     if (LA_TRACE_PTR(a) && lane == 0 && (blockIdx.x == 0 || blockIdx.x == 200)) LA_TRACE_PTR(a)[16 + (blockIdx.x ? 8 : 0) + wave] = wall_clock64();
     if (LA_TRACE_PTR(a) && lane == 0 && blockIdx.x > 2) LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + wave] = wall_clock64();
   } else {
+    __builtin_amdgcn_s_setprio(3);  // (the IO waves' short bursts go first: measured neutral at 32 rows, 1.6 % on the one-row step; the other way round costs 0.8 %)
     io_wave_main<MT, NW>(a, lds0, wave - NW, lane, L);
     // a wait that gave up anywhere in the workgroup: tell the host
     if (lane == 0 && ctl_read(lds0 + NW * Lay<MT, NW>::REG + M_CTL + 4 * K_DEAD) != 0)

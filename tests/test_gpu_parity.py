@@ -569,9 +569,10 @@ def test_teacher_forced_steps_over_relocated_rows(name, Bp):
 
 @pytest.mark.parametrize("name", ["small_bf16", "small_f16"])
 def test_ragged_workgroup_count_and_plain_kernels_agree(monkeypatch, name):
-    """The same block through three builds of the same 16-bit model: all workgroups (the default),
-    a workgroup count that leaves every matrix with a ragged tile split (LA_WGS), and the plain
-    tiled kernels (LA_FORCE_GENERIC): each within the bar of the oracle."""
+    """The same block through several builds of the same 16-bit model: all workgroups (the default),
+    a workgroup count that leaves every matrix with a ragged tile split (LA_WGS), the plain tiled
+    kernels (LA_FORCE_GENERIC) and the earlier LDS-ring kernel (LA_LDS_RING): each within the bar
+    of the oracle."""
     shape = synth.SHAPES[name].with_layers(2)
     L, Bp = 45, 32
     om = oracle_model(shape, seed=3, head=False)
@@ -581,7 +582,10 @@ def test_ragged_workgroup_count_and_plain_kernels_agree(monkeypatch, name):
         okv.fill(l, *synth.kv_fill(shape, l, L, 4))
     okv.L = L
     want = otf.forward_block(om, okv, x, pos, vis)
-    for env in ({}, {"LA_WGS": "37"}, {"LA_FORCE_GENERIC": "1"}):
+    envs = [{}, {"LA_WGS": "37"}, {"LA_FORCE_GENERIC": "1"}]
+    if shape.dtype == "bf16":
+        envs.append({"LA_LDS_RING": "1"})   # the earlier persistent kernel (bfloat16 cache only)
+    for env in envs:
         for k, v in env.items():
             monkeypatch.setenv(k, v)
         eng = gpu_engine(shape, L + Bp, seed=3, head=False)
