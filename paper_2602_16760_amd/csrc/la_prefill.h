@@ -44,6 +44,64 @@ struct PfGemm {
   uint16_t *act;      // GATEUP: operand fragments of the down projection [F/32][RT][64][8]
 };
 
+// The epilogue of a wave's tile: acc[m][j][i] is row 16 (r0 + m) + 4 q4 + i, column c16 of column tile t0 + j.
+template <int MODE, int NTW>
+__device__ __forceinline__ void pf_epilogue(const PfGemm &p, const f32x4 (&acc)[4][NTW], int r0, int t0, int lane) {
+  const int q4 = lane >> 4, c16 = lane & 15;
+#pragma unroll
+  for (int j = 0; j < NTW; ++j) {
+    const int t = t0 + j;
+    if (t >= p.ntiles) continue;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 16 * (r0 + m) + 4 * q4 + i;
+        const float v = acc[m][j][i];
+        if (MODE == PF_RESID) {
+          if (row < p.M) p.x[(size_t)row * p.d + 16 * t + c16] += v;
+        } else if (MODE == PF_GATEUP) {
+          // tile columns: 8 gate channels, then the same 8 channels of up
+          const float rsf = row < p.M ? p.rs[row] : 0.f;
+          const float other = __shfl_xor(v, 8, 64);
+          const float g = v * rsf, u = other * rsf;
+          if (c16 < 8 && row < p.M) {
+            const int ch = 8 * t + c16;
+            const float y = g / (1.0f + __expf(-g)) * u;
+            const uint16_t h = (uint16_t)(pack_f16(y, 0.f) & 0xffffu);
+            p.act[((size_t)frag_piece(ch & ~7, row, p.RT) >> 1) + (ch & 7)] = h;
+          }
+        } else {
+          // tile columns: channels 8 jj .. 8 jj + 7 and dh/2 + 8 jj .. of head hs (both members of eight RoPE pairs)
+          const int spj = p.dh >> 4, half = p.dh >> 1;
+          const int hs = t / spj, jj = t - hs * spj;
+          const float rsf = row < p.M ? p.rs[row] : 0.f;
+          const float mine = v * rsf, other = __shfl_xor(v, 8, 64) * rsf;
+          if (row >= p.M) continue;
+          const int pr = 8 * jj + (c16 & 7);  // pair index inside the head
+          const int ch = c16 < 8 ? pr : half + pr;
+          float y = mine;
+          if (hs < p.Hq + p.Hkv) {
+            const float c = p.cs[((size_t)row * half + pr) * 2], sn = p.cs[((size_t)row * half + pr) * 2 + 1];
+            const float qscale = hs < p.Hq ? 1.0f / sqrtf((float)p.dh) : 1.0f;
+            y = (c16 < 8 ? mine * c - other * sn : mine * c + other * sn) * qscale;
+          }
+          const uint16_t h = kv_bits(p.f16 != 0, y);
+          if (hs < p.Hq) {
+            const int KTq = p.dh >> 5;
+            const size_t frag = ((size_t)hs * p.RT + (row >> 4)) * KTq + (ch >> 5);
+            p.Q[(frag * 64 + (row & 15) + 16 * ((ch & 31) >> 3)) * 8 + (ch & 7)] = h;
+          } else if (hs < p.Hq + p.Hkv) {
+            p.Kc[((size_t)(p.L0 + row) * p.Hkv + (hs - p.Hq)) * p.dh + ch] = h;
+          } else {
+            p.Vc[v_index(true, p.L0 + row, hs - p.Hq - p.Hkv, ch, p.Hkv, p.dh)] = h;
+          }
+        }
+      }
+    }
+  }
+}
+
 // NTW: column tiles per wave (8: 128 columns, for the wide matrices; 4: 64 columns, so that the 4096-column matrices
 // still give every CU a workgroup); NS: k-tiles in flight per wave (NS - 1 requested ahead of the one being multiplied).
 template <int MODE, int NTW, int NS>
@@ -116,59 +174,96 @@ __global__ __launch_bounds__(256) void pf_gemm_kernel(PfGemm p) {
     load(kt, sa[0], sb[0]);
     mul(sa[0], sb[0]);
   }
-  // ---- epilogue: acc[m][j][i] is row 16 (r0 + m) + 4 q4 + i, column c16 of tile t0 + j
+  pf_epilogue<MODE, NTW>(p, acc, r0, t0, lane);
+}
+
+// The same product with the weight fragments shared through LDS: a workgroup's four waves take four consecutive 64-row
+// groups of ONE column group, so the NTW weight fragments of a k-tile are fetched once per workgroup (each wave brings
+// NTW / 4 of them with direct-to-LDS loads into a ring of NS stages) instead of once per wave; the activation fragments
+// stay per wave in registers.  What a CU takes in per k-tile drops from 4 x (4 + NTW) KB to 16 + NTW KB, which is what
+// bounded the first kernel.  One workgroup barrier per k-tile: past it every wave's part of the stage has landed and
+// every wave is done reading the stage that the next requests overwrite.  Needs KT to be a multiple of NS.
+template <int MODE, int NTW, int NS>
+__device__ __forceinline__ void pf_gemm_lds_body(const PfGemm &p, LDS_AS uint8_t *pf_lds) {  // (device-only types: not in the kernel's own body, which the host pass instantiates too)
+  static_assert(NTW % 4 == 0, "every wave brings the same number of weight fragments");
+  constexpr int BW = NTW / 4;       // weight fragments a wave brings per k-tile
+  constexpr int LPS = 4 + BW;       // this wave's requests per stage
+  const int wave = uni((int)(threadIdx.x >> 6)), lane = threadIdx.x & 63;
+  const int n_cg = (p.ntiles + NTW - 1) / NTW, RB = (p.RT / 4 + 3) / 4;
+  const int xcd = (int)blockIdx.x % 8, turn = (int)blockIdx.x / 8;
+  const int rb = turn % RB, cg = (turn / RB) * 8 + xcd;
+  if (cg >= n_cg) return;  // (the whole workgroup)
+  const int rg = rb * 4 + wave;                       // this wave's 64-row group
+  const bool active = rg * 4 < p.RT;
+  const int r0 = active ? rg * 4 : p.RT - 4;          // (a wave without rows runs along on the last group and drops the result)
+  const int t0 = cg * NTW;
+  const unsigned lds0 = (unsigned)(uintptr_t)pf_lds;
+  // the weight fragments this wave brings: column tiles t0 + BW wave .. + BW - 1
+  __amdgpu_buffer_rsrc_t wr[BW];
+  unsigned wof[BW], wnt[BW];
 #pragma unroll
-  for (int j = 0; j < NTW; ++j) {
-    const int t = t0 + j;
-    if (t >= p.ntiles) continue;
+  for (int jj = 0; jj < BW; ++jj) {
+    const int tj = t0 + BW * wave + jj;
+    const int t = tj < p.ntiles ? tj : p.ntiles - 1;
+    const int c = uni(t % p.G), lt = uni(t / p.G);
+    unsigned off = p.frag0;
+    for (int i = 0; i < p.n_prev; ++i) off += (unsigned)((p.prev_ntiles[i] > c ? (p.prev_ntiles[i] - c + p.G - 1) / p.G : 0) * p.prev_KT[i]);
+    wr[jj] = rsrc_of(p.wstream + (size_t)c * p.cu_bytes);
+    wof[jj] = uni((off + (unsigned)lt) * 1024u);
+    wnt[jj] = uni((unsigned)((p.ntiles - c + p.G - 1) / p.G) * 1024u);
+  }
+  const int nk_q = p.KT / p.NW, nk_r = p.KT % p.NW;
+  const uint8_t *ab = (const uint8_t *)p.A + ((size_t)r0 * 64 + (unsigned)lane) * 16u;
+  const size_t a_kt = (size_t)p.RT * 1024u;
+  const unsigned voff = (unsigned)lane * 16u;
+  auto request = [&](int kt, int slot, u32x4 (&a)[4]) {
+    const int w = kt % p.NW, i = kt / p.NW;
+    const unsigned row = (unsigned)(w * nk_q + (w < nk_r ? w : nk_r) + i);
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
+    for (int jj = 0; jj < BW; ++jj)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(wr[jj], (LDS_AS void *)(uintptr_t)(lds0 + (unsigned)((slot * NTW + BW * wave + jj) * 1024)), 16, voff,
+                                               uni(wof[jj] + row * wnt[jj]), 0, 0);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 16 * (r0 + m) + 4 * q4 + i;
-        const float v = acc[m][j][i];
-        if (MODE == PF_RESID) {
-          if (row < p.M) p.x[(size_t)row * p.d + 16 * t + c16] += v;
-        } else if (MODE == PF_GATEUP) {
-          // tile columns: 8 gate channels, then the same 8 channels of up
-          const float rsf = row < p.M ? p.rs[row] : 0.f;
-          const float other = __shfl_xor(v, 8, 64);
-          const float g = v * rsf, u = other * rsf;
-          if (c16 < 8 && row < p.M) {
-            const int ch = 8 * t + c16;
-            const float y = g / (1.0f + __expf(-g)) * u;
-            const uint16_t h = (uint16_t)(pack_f16(y, 0.f) & 0xffffu);
-            p.act[((size_t)frag_piece(ch & ~7, row, p.RT) >> 1) + (ch & 7)] = h;
-          }
-        } else {
-          // tile columns: channels 8 jj .. 8 jj + 7 and dh/2 + 8 jj .. of head hs (both members of eight RoPE pairs)
-          const int spj = p.dh >> 4, half = p.dh >> 1;
-          const int hs = t / spj, jj = t - hs * spj;
-          const float rsf = row < p.M ? p.rs[row] : 0.f;
-          const float mine = v * rsf, other = __shfl_xor(v, 8, 64) * rsf;
-          if (row >= p.M) continue;
-          const int pr = 8 * jj + (c16 & 7);  // pair index inside the head
-          const int ch = c16 < 8 ? pr : half + pr;
-          float y = mine;
-          if (hs < p.Hq + p.Hkv) {
-            const float c = p.cs[((size_t)row * half + pr) * 2], sn = p.cs[((size_t)row * half + pr) * 2 + 1];
-            const float qscale = hs < p.Hq ? 1.0f / sqrtf((float)p.dh) : 1.0f;
-            y = (c16 < 8 ? mine * c - other * sn : mine * c + other * sn) * qscale;
-          }
-          const uint16_t h = kv_bits(p.f16 != 0, y);
-          if (hs < p.Hq) {
-            const int KTq = p.dh >> 5;
-            const size_t frag = ((size_t)hs * p.RT + (row >> 4)) * KTq + (ch >> 5);
-            p.Q[(frag * 64 + (row & 15) + 16 * ((ch & 31) >> 3)) * 8 + (ch & 7)] = h;
-          } else if (hs < p.Hq + p.Hkv) {
-            p.Kc[((size_t)(p.L0 + row) * p.Hkv + (hs - p.Hq)) * p.dh + ch] = h;
-          } else {
-            p.Vc[v_index(true, p.L0 + row, hs - p.Hq - p.Hkv, ch, p.Hkv, p.dh)] = h;
-          }
-        }
-      }
+    for (int m = 0; m < 4; ++m) a[m] = *(const u32x4 *)(ab + (size_t)kt * a_kt + (unsigned)m * 1024u);
+  };
+  f32x4 acc[4][NTW];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int j = 0; j < NTW; ++j) acc[m][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  u32x4 sa[NS][4];
+  const int last_kt = p.KT - 1;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) request(s < last_kt ? s : last_kt, s, sa[s]);
+  for (int kt0 = 0; kt0 < p.KT; kt0 += NS) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      wait_vmcnt<(NS - 2) * LPS>();        // this wave's requests of stage s are in (the NS - 2 younger stages may be out)
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);
+      __builtin_amdgcn_s_barrier();        // ... and everybody's; the stage before is read by nobody any more
+      __atomic_signal_fence(__ATOMIC_SEQ_CST);  // (compiler fences: no LDS read moves across the barrier; no hardware wait for memory is wanted here)
+      const int nx = kt0 + s + NS - 1;
+      request(nx < last_kt ? nx : last_kt, (s + NS - 1) % NS, sa[(s + NS - 1) % NS]);
+      __builtin_amdgcn_sched_barrier(0);
+      u32x4 b[NTW];
+#pragma unroll
+      for (int j = 0; j < NTW; ++j) b[j] = *(LDS_AS const u32x4 *)(uintptr_t)(lds0 + (unsigned)((s * NTW + j) * 1024) + voff);
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int j = 0; j < NTW; ++j)
+          acc[m][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, sa[s][m]), __builtin_bit_cast(f16x8, b[j]), acc[m][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
+  wait_vmcnt<0>();  // (the requests past the last k-tile land before the LDS is given back)
+  if (active) pf_epilogue<MODE, NTW>(p, acc, r0, t0, lane);
+}
+
+template <int MODE, int NTW, int NS>
+__global__ __launch_bounds__(256) void pf_gemm_lds_kernel(PfGemm p) {
+  extern __shared__ __attribute__((aligned(1024))) uint8_t pf_lds[];
+  pf_gemm_lds_body<MODE, NTW, NS>(p, (LDS_AS uint8_t *)pf_lds);
 }
 
 // Row factors rsqrt(mean x^2 + eps) and the operand fragments of x * gain; one workgroup per row.  Rows M .. 16 RT4 - 1
@@ -337,9 +432,15 @@ static int pf_alloc(la_model *m, PfBuffers &b) {
 
 template <int MODE, int NTW, int NS>
 static int pf_launch_gemm(const PfGemm &p, hipStream_t s, const char *name) {
-  const int n_cg = (p.ntiles + NTW - 1) / NTW, n_cg4 = (n_cg + 3) / 4, row_groups = p.RT / 4;
+  const int n_cg = (p.ntiles + NTW - 1) / NTW;
   ProfScope ps(name, s);
-  pf_gemm_kernel<MODE, NTW, NS><<<row_groups * ((n_cg4 + 7) / 8 * 8), 256, 0, s>>>(p);
+  if (p.KT % NS == 0 && p.KT >= NS) {  // weight fragments shared through LDS
+    const int RB = (p.RT / 4 + 3) / 4;
+    pf_gemm_lds_kernel<MODE, NTW, NS><<<RB * ((n_cg + 7) / 8 * 8), 256, NS * NTW * 1024, s>>>(p);
+  } else {
+    const int n_cg4 = (n_cg + 3) / 4, row_groups = p.RT / 4;
+    pf_gemm_kernel<MODE, NTW, NS><<<row_groups * ((n_cg4 + 7) / 8 * 8), 256, 0, s>>>(p);
+  }
   LA_HIP(hipGetLastError());
   return LA_OK;
 }
