@@ -44,7 +44,10 @@ struct PfGemm {
   uint16_t *act;      // GATEUP: operand fragments of the down projection [F/32][RT][64][8]
 };
 
-// The epilogue of a wave's tile: acc[m][j][i] is row 16 (r0 + m) + 4 q4 + i, column c16 of column tile t0 + j.
+// The epilogue of a wave's tile.  The products are formed with the weight fragment as the MFMA's first operand, so
+// a lane holds FOUR CONSECUTIVE COLUMNS of one row: acc[m][j][i] is row 16 (r0 + m) + c16, column 4 q4 + i of column
+// tile t0 + j.  Every store is then an 8- or 16-byte vector (the cache's V layout aside), and the partner of a RoPE
+// pair or of a gate channel (8 columns further) sits 32 lanes further.
 template <int MODE, int NTW>
 __device__ __forceinline__ void pf_epilogue(const PfGemm &p, const f32x4 (&acc)[4][NTW], int r0, int t0, int lane) {
   const int q4 = lane >> 4, c16 = lane & 15;
@@ -54,47 +57,62 @@ __device__ __forceinline__ void pf_epilogue(const PfGemm &p, const f32x4 (&acc)[
     if (t >= p.ntiles) continue;
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
+      const int row = 16 * (r0 + m) + c16;
+      const f32x4 v = acc[m][j];
+      if (MODE == PF_RESID) {
+        if (row < p.M) {
+          f32x4 *xp = reinterpret_cast<f32x4 *>(p.x + (size_t)row * p.d + 16 * t + 4 * q4);
+          *xp = *xp + v;
+        }
+      } else {
+        const float rsf = row < p.M ? p.rs[row] : 0.f;
+        f32x4 other;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = 16 * (r0 + m) + 4 * q4 + i;
-        const float v = acc[m][j][i];
-        if (MODE == PF_RESID) {
-          if (row < p.M) p.x[(size_t)row * p.d + 16 * t + c16] += v;
-        } else if (MODE == PF_GATEUP) {
-          // tile columns: 8 gate channels, then the same 8 channels of up
-          const float rsf = row < p.M ? p.rs[row] : 0.f;
-          const float other = __shfl_xor(v, 8, 64);
-          const float g = v * rsf, u = other * rsf;
-          if (c16 < 8 && row < p.M) {
-            const int ch = 8 * t + c16;
-            const float y = g / (1.0f + __expf(-g)) * u;
-            const uint16_t h = (uint16_t)(pack_f16(y, 0.f) & 0xffffu);
-            p.act[((size_t)frag_piece(ch & ~7, row, p.RT) >> 1) + (ch & 7)] = h;
+        for (int i = 0; i < 4; ++i) other[i] = __shfl_xor(v[i], 32, 64);
+        if (row >= p.M) continue;
+        if (MODE == PF_GATEUP) {
+          // tile columns: 8 gate channels (lanes q4 = 0, 1), then the same 8 channels of up (q4 = 2, 3)
+          if (q4 < 2) {
+            float y[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float g = v[i] * rsf, u = other[i] * rsf;
+              y[i] = g / (1.0f + __expf(-g)) * u;
+            }
+            const int ch = 8 * t + 4 * q4;
+            *(u32x2 *)((uint8_t *)p.act + frag_piece(ch & ~7, row, p.RT) + 8 * (q4 & 1)) = u32x2{pack_f16(y[0], y[1]), pack_f16(y[2], y[3])};
           }
         } else {
-          // tile columns: channels 8 jj .. 8 jj + 7 and dh/2 + 8 jj .. of head hs (both members of eight RoPE pairs)
+          // tile columns: channels 8 jj .. 8 jj + 7 (q4 = 0, 1) and dh/2 + 8 jj .. (q4 = 2, 3) of head hs: eight RoPE pairs
           const int spj = p.dh >> 4, half = p.dh >> 1;
           const int hs = t / spj, jj = t - hs * spj;
-          const float rsf = row < p.M ? p.rs[row] : 0.f;
-          const float mine = v * rsf, other = __shfl_xor(v, 8, 64) * rsf;
-          if (row >= p.M) continue;
-          const int pr = 8 * jj + (c16 & 7);  // pair index inside the head
-          const int ch = c16 < 8 ? pr : half + pr;
-          float y = mine;
+          const int pr = 8 * jj + 4 * (q4 & 1);  // first of this lane's four pairs
+          const int ch = q4 < 2 ? pr : half + pr;
+          const bool h16 = p.f16 != 0;
+          float y[4];
           if (hs < p.Hq + p.Hkv) {
-            const float c = p.cs[((size_t)row * half + pr) * 2], sn = p.cs[((size_t)row * half + pr) * 2 + 1];
             const float qscale = hs < p.Hq ? 1.0f / sqrtf((float)p.dh) : 1.0f;
-            y = (c16 < 8 ? mine * c - other * sn : mine * c + other * sn) * qscale;
+            const f32x4 *csp = reinterpret_cast<const f32x4 *>(p.cs + ((size_t)row * half + pr) * 2);
+            const f32x4 cs0 = csp[0], cs1 = csp[1];  // (cos, sin) of pairs pr .. pr + 3
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float c = i < 2 ? cs0[2 * i] : cs1[2 * (i - 2)], sn = i < 2 ? cs0[2 * i + 1] : cs1[2 * (i - 2) + 1];
+              const float mine = v[i] * rsf, oth = other[i] * rsf;
+              y[i] = (q4 < 2 ? mine * c - oth * sn : mine * c + oth * sn) * qscale;
+            }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) y[i] = v[i] * rsf;
           }
-          const uint16_t h = kv_bits(p.f16 != 0, y);
           if (hs < p.Hq) {
             const int KTq = p.dh >> 5;
             const size_t frag = ((size_t)hs * p.RT + (row >> 4)) * KTq + (ch >> 5);
-            p.Q[(frag * 64 + (row & 15) + 16 * ((ch & 31) >> 3)) * 8 + (ch & 7)] = h;
+            *(u32x2 *)(p.Q + (frag * 64 + (row & 15) + 16 * ((ch & 31) >> 3)) * 8 + (ch & 7)) = u32x2{pack_kv(h16, y[0], y[1]), pack_kv(h16, y[2], y[3])};
           } else if (hs < p.Hq + p.Hkv) {
-            p.Kc[((size_t)(p.L0 + row) * p.Hkv + (hs - p.Hq)) * p.dh + ch] = h;
+            *(u32x2 *)(p.Kc + ((size_t)(p.L0 + row) * p.Hkv + (hs - p.Hq)) * p.dh + ch) = u32x2{pack_kv(h16, y[0], y[1]), pack_kv(h16, y[2], y[3])};
           } else {
-            p.Vc[v_index(true, p.L0 + row, hs - p.Hq - p.Hkv, ch, p.Hkv, p.dh)] = h;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p.Vc[v_index(true, p.L0 + row, hs - p.Hq - p.Hkv, ch + i, p.Hkv, p.dh)] = kv_bits(h16, y[i]);
           }
         }
       }
@@ -151,7 +169,7 @@ __global__ __launch_bounds__(256) void pf_gemm_kernel(PfGemm p) {
     for (int m = 0; m < 4; ++m)
 #pragma unroll
       for (int j = 0; j < NTW; ++j)
-        acc[m][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a[m]), __builtin_bit_cast(f16x8, b[j]), acc[m][j], 0, 0, 0);
+        acc[m][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, b[j]), __builtin_bit_cast(f16x8, a[m]), acc[m][j], 0, 0, 0);
   };
   // A window of NS k-tiles: stage s holds k-tile kt with kt % NS == s (all indices are constants after unrolling).
   // The loop body has no branch (requests past the last k-tile repeat it and are never used): with a branch around a
@@ -252,7 +270,7 @@ __device__ __forceinline__ void pf_gemm_lds_body(const PfGemm &p, LDS_AS uint8_t
       for (int m = 0; m < 4; ++m)
 #pragma unroll
         for (int j = 0; j < NTW; ++j)
-          acc[m][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, sa[s][m]), __builtin_bit_cast(f16x8, b[j]), acc[m][j], 0, 0, 0);
+          acc[m][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, b[j]), __builtin_bit_cast(f16x8, sa[s][m]), acc[m][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
