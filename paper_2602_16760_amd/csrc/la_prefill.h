@@ -20,7 +20,8 @@ namespace la {
 
 constexpr int PF_ROWS = 1024;  // rows of one prompt chunk (buffers are sized for it)
 constexpr int PF_MIN = 128;    // shorter prompts go through the block kernel
-constexpr int PF_NS = 4;       // k-tiles a wave of the matrix product keeps in flight
+constexpr int PF_NS = 4;       // k-tiles a wave of the matrix product keeps in flight: all operands in registers
+constexpr int PF_NS_LDS = 8;   // ... weight fragments through LDS (a step takes half the memory latency at four, measured)
 
 enum PfMode { PF_QKV = 0, PF_RESID = 1, PF_GATEUP = 2 };
 
@@ -448,16 +449,16 @@ static int pf_alloc(la_model *m, PfBuffers &b) {
 }
 
 
-template <int MODE, int NTW, int NS>
+template <int MODE, int NTW>
 static int pf_launch_gemm(const PfGemm &p, hipStream_t s, const char *name) {
   const int n_cg = (p.ntiles + NTW - 1) / NTW;
   ProfScope ps(name, s);
-  if (p.KT % NS == 0 && p.KT >= NS) {  // weight fragments shared through LDS
+  if (p.KT % PF_NS_LDS == 0) {  // weight fragments shared through LDS
     const int RB = (p.RT / 4 + 3) / 4;
-    pf_gemm_lds_kernel<MODE, NTW, NS><<<RB * ((n_cg + 7) / 8 * 8), 256, NS * NTW * 1024, s>>>(p);
+    pf_gemm_lds_kernel<MODE, NTW, PF_NS_LDS><<<RB * ((n_cg + 7) / 8 * 8), 256, PF_NS_LDS * NTW * 1024, s>>>(p);
   } else {
     const int n_cg4 = (n_cg + 3) / 4, row_groups = p.RT / 4;
-    pf_gemm_kernel<MODE, NTW, NS><<<row_groups * ((n_cg4 + 7) / 8 * 8), 256, 0, s>>>(p);
+    pf_gemm_kernel<MODE, NTW, PF_NS><<<row_groups * ((n_cg4 + 7) / 8 * 8), 256, 0, s>>>(p);
   }
   LA_HIP(hipGetLastError());
   return LA_OK;
@@ -524,7 +525,7 @@ int mfma_prefill_chunk(la_model *m, la_kv *kv, const int32_t *tok, int M, int L0
     }
     PfGemm p = gemm_args(0);
     p.A = b.A;
-    if ((rc = pf_launch_gemm<PF_QKV, 8, PF_NS>(p, s, "pf_gemm_qkv"))) return rc;
+    if ((rc = pf_launch_gemm<PF_QKV, 8>(p, s, "pf_gemm_qkv"))) return rc;
     {
       ProfScope ps("pf_attn", s);
       const int grid = ceil_div(RTr * d.n_q_heads, 4);
@@ -539,17 +540,17 @@ int mfma_prefill_chunk(la_model *m, la_kv *kv, const int32_t *tok, int M, int L0
     }
     p = gemm_args(1);
     p.A = b.attn;
-    if ((rc = pf_launch_gemm<PF_RESID, 4, PF_NS>(p, s, "pf_gemm_o"))) return rc;
+    if ((rc = pf_launch_gemm<PF_RESID, 4>(p, s, "pf_gemm_o"))) return rc;
     {
       ProfScope ps("pf_prep", s);
       pf_prep_kernel<<<16 * RT, 256, 0, s>>>(b.x, m->layers[l].g_mlp, M, d.d_model, RT, d.rms_eps, b.rs, b.A);
     }
     p = gemm_args(2);
     p.A = b.A;
-    if ((rc = pf_launch_gemm<PF_GATEUP, 8, PF_NS>(p, s, "pf_gemm_gateup"))) return rc;
+    if ((rc = pf_launch_gemm<PF_GATEUP, 8>(p, s, "pf_gemm_gateup"))) return rc;
     p = gemm_args(3);
     p.A = b.act;
-    if ((rc = pf_launch_gemm<PF_RESID, 4, PF_NS>(p, s, "pf_gemm_down"))) return rc;
+    if ((rc = pf_launch_gemm<PF_RESID, 4>(p, s, "pf_gemm_down"))) return rc;
   }
   LA_HIP(hipGetLastError());
   return LA_OK;
