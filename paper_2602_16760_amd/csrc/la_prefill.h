@@ -21,7 +21,7 @@ namespace la {
 constexpr int PF_ROWS = 1024;  // rows of one prompt chunk (buffers are sized for it)
 constexpr int PF_MIN = 128;    // shorter prompts go through the block kernel
 constexpr int PF_NS = 4;       // k-tiles a wave of the matrix product keeps in flight: all operands in registers
-constexpr int PF_NS_LDS = 8;   // ... weight fragments through LDS (a step takes half the memory latency at four, measured)
+constexpr int PF_NS_LDS = 4;   // ... weight fragments through LDS (a step takes half the memory latency at four, measured)
 
 enum PfMode { PF_QKV = 0, PF_RESID = 1, PF_GATEUP = 2 };
 
@@ -525,7 +525,7 @@ int mfma_prefill_chunk(la_model *m, la_kv *kv, const int32_t *tok, int M, int L0
     }
     PfGemm p = gemm_args(0);
     p.A = b.A;
-    if ((rc = pf_launch_gemm<PF_QKV, 8>(p, s, "pf_gemm_qkv"))) return rc;
+    if ((rc = pf_launch_gemm<PF_QKV, 4>(p, s, "pf_gemm_qkv"))) return rc;
     {
       ProfScope ps("pf_attn", s);
       const int grid = ceil_div(RTr * d.n_q_heads, 4);
@@ -547,7 +547,7 @@ int mfma_prefill_chunk(la_model *m, la_kv *kv, const int32_t *tok, int M, int L0
     }
     p = gemm_args(2);
     p.A = b.A;
-    if ((rc = pf_launch_gemm<PF_GATEUP, 8>(p, s, "pf_gemm_gateup"))) return rc;
+    if ((rc = pf_launch_gemm<PF_GATEUP, 4>(p, s, "pf_gemm_gateup"))) return rc;
     p = gemm_args(3);
     p.A = b.act;
     if ((rc = pf_launch_gemm<PF_RESID, 4>(p, s, "pf_gemm_down"))) return rc;
