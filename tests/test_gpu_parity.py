@@ -82,6 +82,30 @@ def test_forward_layers_matches_oracle(name, nl, L, wng, Bp, n_cand):
         eng.close()
 
 
+def test_residual_stream_near_the_half_precision_limit():
+    """The matrix-core path multiplies x * gain (not the normalised row: the row factor is applied
+    after the product) as IEEE half, which saturates at 65504.  A residual stream whose largest
+    entries sit at about half that limit must still meet the bar, relative to its own size."""
+    shape = synth.SHAPES["small_bf16"].with_layers(2)
+    L, Bp = 64, 32
+    om = oracle_model(shape, seed=3, head=False)
+    okv = otf.KVCache(shape, L + Bp)
+    eng = gpu_engine(shape, L + Bp, seed=3, head=False)
+    try:
+        prefill_both(shape, eng, okv, L, seed=4)
+        x, pos, vis = _block_inputs(shape, L, 5, 4, 5, Bp, 3, seed=5)
+        x = x * np.float32(5000.0)                     # |x| up to ~2.2e4, x * gain up to ~3.3e4
+        assert 2.0e4 < np.max(np.abs(x)) * 1.5 < 6.0e4
+        want = otf.forward_block(om, okv, x, pos, vis)
+        got = eng.forward(x, pos, vis)
+        # the layers add O(1) to a stream of O(1e4): judge what they added, not the stream
+        err = row_rel_err(got.astype(np.float64) - x, want - x)
+        print(f"residual stream x 5000: max row rel err of the two layers' update {err.max():.3e}")
+        assert err.max() <= TOL["bf16"]
+    finally:
+        eng.close()
+
+
 @pytest.mark.parametrize("name", ["tiny_f32", "small_bf16"])
 def test_layer_ranges_compose(name):
     """Layers [0, 1) then [1, n) in two calls give bit for bit what [0, n) gives in one (the paper's
