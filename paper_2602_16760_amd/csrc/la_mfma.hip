@@ -249,6 +249,14 @@ int mfma_create(la_model *m) {
   f->p_gu = make_plan(2 * d.d_ffn, d.d_model, f->n_wgs);
   f->p_down = make_plan(d.d_model, d.d_ffn, f->n_wgs);
   f->p_un = make_plan(d.vocab, d.d_model, f->n_wgs);
+  if (f->use_r)  // the MFMA waves' schedule tables hold a fixed number of entries per layer (and for the unembedding)
+    for (int ntmax : {rs::Geo<1>::NTMAX, rs::Geo<4>::NTMAX}) {
+      auto nb = [&](const GemmPlan &p) { return rs::schedule_bodies(p.KT, p.nt_max, p.ntp, ntmax, R_NW); };
+      const int layer = nb(f->p_qkv) + nb(f->p_o) + nb(f->p_gu) + nb(f->p_down), un = nb(f->p_un);
+      LA_REQUIRE(layer <= rs::TAB_MAX && un <= rs::TAB_MAX, LA_EINVAL,
+                 "the register-streaming kernel's schedule has %d entries per layer and %d for the unembedding; it holds %d (LA_LDS_RING=1 "
+                 "selects the other kernel)", layer, un, rs::TAB_MAX);
+    }
   f->seg_frags = (unsigned)(f->p_qkv.nt_max * f->p_qkv.KT + f->p_o.nt_max * f->p_o.KT + f->p_gu.nt_max * f->p_gu.KT +
                             f->p_down.nt_max * f->p_down.KT);
   f->seg_frags = (f->seg_frags + CHUNK - 1) / CHUNK * CHUNK;  // the producer moves whole chunks
@@ -418,9 +426,9 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       const unsigned long long t0 = h[S * q];
       auto rel = [&](int k) { return h[S * q + k] > t0 ? (h[S * q + k] - t0) * 0.01 : -1.0; };
       double since_prev = q > 0 ? (t0 - h[S * (q - 1) + 2]) * 0.01 : 0.0;
-      fprintf(stderr, "[la trace]   phase %2d: +%5.2f | k-loop end %6.2f (waited for weights %6.2f) tile %6.2f epilogue %6.2f | attn: loads %6.2f loop %6.2f merged %6.2f | "
+      fprintf(stderr, "[la trace]   phase %2d: +%5.2f | k-loop end %6.2f (waited for weights %6.2f) tile %6.2f epilogue %6.2f | pass entry %6.2f first operand %6.2f next pass %6.2f | "
               "work end %6.2f | barrier: stores %6.2f waves %6.2f released %6.2f\n", q, since_prev, rel(1), h[S * q + 1] > t0 ? h[S * q + 3] * 0.01 : -1.0,
-              rel(4), rel(5), rel(9), rel(10), rel(11), rel(2), rel(6), rel(7), rel(8));
+              rel(4), rel(5), rel(10), rel(9), rel(11), rel(2), rel(6), rel(7), rel(8));
       if (h[S * q + 14]) {
         fprintf(stderr, "[la trace]             attention per wave (loads issued / first block landed / blocks done):");
         for (int w = 0; w < NCW; ++w) fprintf(stderr, " %.2f/%.2f/%.2f", rel(16 + w), rel(24 + w), rel(32 + w));

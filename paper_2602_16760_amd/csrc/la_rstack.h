@@ -92,6 +92,8 @@ struct Pass {
 };
 
 __device__ __forceinline__ int slots_for(int nt) { return nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8; }
+// k-tiles of one body of a pass with NTS slots per k-tile
+__device__ __forceinline__ int body_rows(int NTS) { return RING_D / NTS; }
 
 // Walks the passes of a launch in order (uniform values only; plain integers, picked by
 // comparisons: an indexed array or a selected struct would live in scratch memory, and an MFMA
@@ -219,7 +221,7 @@ struct BodyCursor {
   // real slots of the current body: slot j <-> (k-tile i0 + j / NTS, tile j % NTS)
   __device__ __forceinline__ unsigned mask() const {
     if (pw.done) return 0u;
-    const int NTS = pw.cur.NTS, DK = RING_D / NTS;
+    const int NTS = pw.cur.NTS, DK = body_rows(NTS);
     const int left = nk - i0;
     const int rows = left < DK ? (left > 0 ? left : 0) : DK;
     const unsigned rowmask = (1u << pw.cur.NT) - 1u;
@@ -228,7 +230,7 @@ struct BodyCursor {
     return m;
   }
   __device__ __forceinline__ void next_body() {  // (only while !pass_finished())
-    i0 += RING_D / pw.cur.NTS;
+    i0 += body_rows(pw.cur.NTS);
   }
   __device__ __forceinline__ void next_pass() {
     a_seq0 += (unsigned)nk;
@@ -258,6 +260,21 @@ constexpr int TAB_MAX = 128;       // bodies of one MFMA wave per layer
 constexpr int TAB_HDR = 16;        // per wave: {bodies, operand k-tiles per layer, passes per layer, 0}
 constexpr int TAB_BYTES = TAB_HDR + TAB_MAX * 20;
 
+// Host: bodies of one GEMM in an MFMA wave's schedule, at most (the workgroup with the most column tiles, the wave
+// with the most k-tiles), for passes of up to ntmax tiles.  The tables hold TAB_MAX bodies per layer.
+inline int schedule_bodies(int KT, int nt_max, int ntp, int ntmax, int NW) {
+  const int step = ntp < ntmax ? ntp : ntmax;
+  const int nk = (KT + NW - 1) / NW;
+  int n = 0;
+  for (int t0 = 0; t0 < nt_max; t0 += step) {
+    const int NT = nt_max - t0 < step ? nt_max - t0 : step;
+    const int NTS = NT <= 1 ? 1 : NT <= 2 ? 2 : NT <= 4 ? 4 : 8;
+    const int b = (nk * NTS + RING_D - 1) / RING_D;
+    n += b > 1 ? b : 1;
+  }
+  return n;
+}
+
 template <int NW>
 __device__ __forceinline__ void build_schedule(const StackArgs &a, int ntmax, int w, unsigned tab) {
   // one layer's worth: layers lb .. lb + 1 of a stack launch, or the unembedding
@@ -278,7 +295,7 @@ __device__ __forceinline__ void build_schedule(const StackArgs &a, int ntmax, in
       c.next_pass();
       continue;
     }
-    const int DK = RING_D / c.pw.cur.NTS;
+    const int DK = body_rows(c.pw.cur.NTS);
     const int rows = c.nk - c.i0 < DK ? c.nk - c.i0 : DK;
     const bool last = c.i0 + DK >= c.nk;
     if (n < TAB_MAX) {
@@ -293,7 +310,7 @@ __device__ __forceinline__ void build_schedule(const StackArgs &a, int ntmax, in
     c.next_body();
     if (c.pass_finished()) c.next_pass();
   }
-  hdr[0] = (unsigned)n;      // (more than TAB_MAX: the host does not launch this kernel for such a shape)
+  hdr[0] = (unsigned)n;      // (more than TAB_MAX: the host refuses such a shape when the model is created)
   hdr[1] = c.a_seq0;         // operand k-tiles of this wave per layer
   hdr[2] = c.pseq;           // passes per layer
   hdr[3] = 0u;
@@ -320,62 +337,82 @@ __device__ __forceinline__ unsigned m_wait_ge(unsigned ctl, int word, unsigned w
 // same straight-line code serves every pass.  With fewer than NTMAX slots per k-tile an
 // accumulator therefore holds the sum over every (NTMAX >> lg)-th k-tile of one column tile, and the
 // partial tile is the sum of the accumulators of a tile (dump_partial).
-// The operand is read from LDS for four slots at a time (one fragment set per slot, the same one
+// The operand is read from LDS for GQ slots at a time (one fragment set per slot, the same one
 // several times when the slots share a k-tile): one look at the landing counter and one LDS
-// latency per four slots.
+// latency per GQ slots.
+// A wave issues an instruction every four to six cycles, and the weights of a 16-column tile are
+// through the matrix unit in 16 MT cycles: what a slot costs is its instruction count.  So
+// everything that depends on the slot number alone is worked out once per body, ALL SLOTS AT ONCE,
+// lane j for slot j (where the next occupant of the slot lies in the stream, where the slot's
+// operand k-tile lies in LDS, and per group of GQ slots whether it fetches the operand, which
+// landing count it needs and which count it acknowledges); a slot then takes its values out of
+// these vectors with one v_readlane each.
 template <int MT, int NW>
-__device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT][Geo<MT>::NTMAX], u32x4 rsrc, unsigned lane16, unsigned mask, int lg,
-                                          unsigned a_seq, unsigned ctl, unsigned region, int w, unsigned next_mask, unsigned next_frag,
-                                          unsigned next_stride, int next_lg) {
+__device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT][Geo<MT>::NTMAX], u32x4 rsrc, int lane, bool no_weights, unsigned mask,
+                                          int lg, unsigned a_seq, unsigned ctl, unsigned region, int w, unsigned next_mask, unsigned next_frag,
+                                          unsigned next_stride, int next_lg, unsigned &seen) {
   constexpr int RS = Lay<MT, NW>::RS, AM = Geo<MT>::NTMAX - 1;
   constexpr int GQ = MT <= 3 ? 4 : 2;  // slots per operand fetch (GQ x MT fragments in registers)
-  unsigned seen = 0;  // operand k-tiles known to have landed (sequence number + 1)
+  constexpr int NG = RING_D / GQ;
+  static_assert((RS & (RS - 1)) == 0 && RING_D == 32, "ring slot by masking; one slot per lane of a half wave");
+  const unsigned lane16 = (unsigned)lane * 16u;
+  // -- per slot (lane j) --
+  const unsigned j_l = (unsigned)lane & 31u;
+  // byte offset in this CU's stream of the slot's next occupant (slot j of the body one turn ahead), or out of range (no
+  // traffic, zeros come back)
+  const unsigned v_w = (((next_mask >> j_l) & 1u) && !no_weights)
+                           ? (next_frag + (j_l >> next_lg) * next_stride + (j_l & ((1u << next_lg) - 1u))) * 1024u
+                           : OOB;
+  // LDS address of the slot's operand k-tile
+  const unsigned v_a = region + ((a_seq + (j_l >> lg)) & (unsigned)(RS - 1)) * (unsigned)(MT * 1024);
+  // -- per group (lane q) --
+  const unsigned q_l = (unsigned)lane & (unsigned)(NG - 1);
+  const unsigned g0 = (unsigned)GQ * q_l;
+  const unsigned qm_l = (mask >> g0) & ((1u << GQ) - 1u);
+  // (a group that lies inside the k-tile of the group before it keeps that group's fragments)
+  const bool same_kt = q_l > 0 && (((g0 - 1u) >> lg) == ((g0 + (unsigned)GQ - 1u) >> lg)) && ((mask >> (g0 - 1u)) & 1u);
+  const unsigned pos = g0 + (unsigned)(31 - __builtin_clz(qm_l ? qm_l : 1u));  // the group's last real slot
+  // k-tiles of this body that no later slot needs once the group has its operand: everything in front of the next real
+  // slot's k-tile
+  const unsigned rest = pos + 1u < 32u ? mask >> (pos + 1u) : 0u;
+  const unsigned fin = rest ? ((pos + 1u + (unsigned)__builtin_ctz(rest)) >> lg) : ((pos >> lg) + 1u);
+  const unsigned v_need = (qm_l != 0 && !same_kt) ? a_seq + (pos >> lg) + 1u : 0u;  // 0: no fetch (sequence numbers + 1 are never 0)
+  const unsigned v_fin = a_seq + fin;
+
   u32x4 av[GQ][MT];
 #pragma unroll
   for (int i = 0; i < GQ; ++i)
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) av[i][mt] = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-  for (int q = 0; q < RING_D / GQ; ++q) {
-    const unsigned qm = (mask >> (GQ * q)) & ((1u << GQ) - 1u);
-    // (a group that lies inside the k-tile of the group before it keeps that group's fragments)
-    const bool same_kt = q > 0 && (((unsigned)(GQ * q - 1) >> lg) == ((unsigned)(GQ * q + GQ - 1) >> lg)) && ((mask >> (GQ * q - 1)) & 1u);
-    if (qm != 0 && !same_kt) {
-      const int last = 31 - __builtin_clz(qm);  // the quartet's last real slot
-      const unsigned need = uni(a_seq + ((unsigned)(GQ * q + last) >> lg) + 1u);
+  for (int q = 0; q < NG; ++q) {
+    const unsigned need = (unsigned)__builtin_amdgcn_readlane((int)v_need, q);
+    if (need != 0) {
       if ((int)(seen - need) < 0) seen = m_wait_ge(ctl, K_ALAND + w, need);
 #pragma unroll
       for (int i = 0; i < GQ; ++i) {
-        const unsigned seq = uni(a_seq + ((unsigned)(GQ * q + i) >> lg));
-        const unsigned slot = uni(seq % (unsigned)RS);
+        const unsigned ad = (unsigned)__builtin_amdgcn_readlane((int)v_a, GQ * q + i) + lane16;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) av[i][mt] = *(LDS_AS const u32x4 *)(uintptr_t)(region + (slot * MT + mt) * 1024u + lane16);
+        for (int mt = 0; mt < MT; ++mt) av[i][mt] = *(LDS_AS const u32x4 *)(uintptr_t)(ad + (unsigned)mt * 1024u);
       }
-      // k-tiles of this body that no later slot needs: everything in front of the next real slot's
-      // k-tile (the reads above are in the LDS queue before this write, so when the IO wave
-      // sees it, the operand slots have been read)
-      const unsigned rest = GQ * q + last + 1 < 32 ? mask >> (GQ * q + last + 1) : 0u;
-      const unsigned fin = rest ? ((unsigned)(GQ * q + last + 1 + __builtin_ctz(rest)) >> lg) : (((unsigned)(GQ * q + last) >> lg) + 1u);
+      // (the reads above are in the LDS queue before this write, so when the IO wave sees it, the operand slots have
+      // been read)
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
-      *(volatile LDS_AS unsigned *)(uintptr_t)(ctl + 4 * (K_ADONE + w)) = uni(a_seq + fin);
+      *(volatile LDS_AS unsigned *)(uintptr_t)(ctl + 4 * (K_ADONE + w)) = (unsigned)__builtin_amdgcn_readlane((int)v_fin, q);
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
     }
 #pragma unroll
     for (int i = 0; i < GQ; ++i) {
       const int j = GQ * q + i;
       ring_wait<RING_D - 1>(ring[j]);
-      if ((qm >> i) & 1u) {
+      if ((mask >> j) & 1u) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           acc[mt][j & AM] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, av[i][mt]), __builtin_bit_cast(f16x8, ring[j]),
                                                                     acc[mt][j & AM], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
-      // the slot's next occupant: slot j of the body one turn ahead, or nothing (requested out of
-      // range: no traffic, zeros come back)
-      const bool real = (next_mask >> j) & 1u;
-      const unsigned nf = next_frag + (unsigned)(j >> next_lg) * next_stride + (unsigned)(j & ((1 << next_lg) - 1));
-      ring_load(ring[j], rsrc, real ? lane16 : OOB, uni(nf * 1024u));
+      ring_load(ring[j], rsrc, (unsigned)__builtin_amdgcn_readlane((int)v_w, j) + lane16, 0u);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -421,6 +458,7 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
   const unsigned tab = misc + M_BYTES + (unsigned)w * TAB_BYTES;
   const unsigned region = lds0 + (unsigned)w * Lay<MT, NW>::REG;
   const unsigned lane16 = (unsigned)lane * 16u;
+  const bool no_weights = (LA_DBG_BITS(a.dbg) & 1) != 0;  // (timing experiment: no weight traffic)
   // buffer resource over this CU's stream
   const uint64_t base = (uint64_t)(a.wstream + (size_t)blockIdx.x * a.cu_bytes);
   u32x4 rsrc;
@@ -445,7 +483,7 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
 #pragma unroll
     for (int j = 0; j < RING_D; ++j) {
       const bool real = (m >> j) & 1u;
-      ring_load(ring[j], rsrc, real ? lane16 : OOB, uni((f0 + (unsigned)(j >> lg) * st + (unsigned)(j & ((1 << lg) - 1))) * 1024u));
+      ring_load(ring[j], rsrc, (real && !no_weights) ? lane16 : OOB, uni((f0 + (unsigned)(j >> lg) * st + (unsigned)(j & ((1 << lg) - 1))) * 1024u));
     }
   }
   f32x4 acc[MT][NTMAX];
@@ -453,6 +491,7 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int t = 0; t < NTMAX; ++t) acc[mt][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  unsigned seen = 0;  // operand k-tiles known to have landed (sequence number + 1)
   for (int l = 0; l < n_layers; ++l) {
     const unsigned seg = seg_first + (unsigned)l * seg_stride;
     for (int e = 0; e < n_ent; ++e) {
@@ -475,7 +514,7 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
       const int nlg = (int)((nw3 >> 16) & 0xffu);
       const bool last = (w4 & 1u) != 0;
       const unsigned pseq = (unsigned)l * p_per_layer + (w4 >> 16);
-      mfma_body<MT, NW>(ring, acc, rsrc, lane16, uni(ent_word(e, 0)), lg, a_seq, ctl, region, w, nm, nf, nst, nlg);
+      mfma_body<MT, NW>(ring, acc, rsrc, lane, no_weights, uni(ent_word(e, 0)), lg, a_seq, ctl, region, w, nm, nf, nst, nlg, seen);
       if (last) {
         // the pass is done for this wave: partial tile to LDS (its operand ring is idle now), tell the IO waves
         dump_partial<MT>(acc, lg, region, lane);
@@ -570,8 +609,93 @@ __device__ __forceinline__ bool io_grid_sync(const StackArgs &a, Io &io, unsigne
 // requested out of range, so every batch counts the same).  Up to RS / GB batches in flight,
 // retired one at a time, which publishes their k-tiles.  (Batches, because one turn of this
 // loop costs about half a microsecond of scalar code whatever it moves.)
+// The MT fragments of one operand k-tile (contiguous in memory and in the ring) with one LDS address and one offset.
+template <int MT, int I = 0>
+__device__ __forceinline__ void operand_ktile(__amdgpu_buffer_rsrc_t ra, unsigned dst, unsigned voff, unsigned soff) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (LDS_AS void *)(uintptr_t)dst, 16, voff, soff, I * 1024, 0);
+  if constexpr (I + 1 < MT) operand_ktile<MT, I + 1>(ra, dst, voff, soff);
+}
+
+// The usual case, one MFMA wave per IO wave, with the loop's cost per k-tile cut down: a whole batch that does not wrap
+// in the ring is requested with constant offsets from one LDS address and one stream offset (three scalar
+// instructions and MT loads per k-tile; with the slot, the validity and the addresses worked out per load it was
+// nineteen, and the down projection waited for its operand), and the ring space is looked up only when the space
+// known from the last look does not cover the batch.
+template <int MT, int NW>
+__device__ __forceinline__ bool load_operand_1(Io &io, const uint16_t *A, int KT, unsigned &a_seq, int dbg) {
+  constexpr int RS = Lay<MT, NW>::RS, GB = RS >= 16 ? 8 : 4, LPB = GB * MT;
+  constexpr int FL0 = RS / GB < 63 / LPB + 1 ? RS / GB : 63 / LPB + 1;  // batches in flight: (FL - 1) LPB loads must fit the counter
+  constexpr int FL = FL0 < 4 ? FL0 : 4;
+  static_assert(RS % GB == 0 && FL >= 1 && (FL - 1) * LPB <= 63 && (RS & (RS - 1)) == 0, "ring and load counter");
+  __amdgpu_buffer_rsrc_t ra = rsrc_of(A);
+  const unsigned voff = (dbg & 4) ? OOB : (unsigned)io.lane * 16u;
+  const int w = io.v;
+  const int nk = nk_of(KT, w, NW), n_batches = (nk + GB - 1) / GB;
+  const unsigned region = io.lds0 + (unsigned)w * Lay<MT, NW>::REG;
+  const unsigned ctl_done = io.ctl + 4 * (K_ADONE + w), ctl_land = io.ctl + 4 * (K_ALAND + w);
+  int issued = 0, retired = 0;  // batches
+  unsigned landed = a_seq;
+  unsigned done = ctl_read(ctl_done);  // operand k-tiles the MFMA wave has read, as last seen
+  auto retire_oldest = [&]() {
+    switch (issued - retired) {
+      case 1: wait_vmcnt<0>(); break;
+      case 2: wait_vmcnt<(1 * LPB > 63 ? 63 : 1 * LPB)>(); break;
+      case 3: wait_vmcnt<(2 * LPB > 63 ? 63 : 2 * LPB)>(); break;
+      default: wait_vmcnt<(3 * LPB > 63 ? 63 : 3 * LPB)>(); break;
+    }
+    const int left = nk - retired * GB;
+    landed += (unsigned)(left > GB ? GB : left);
+    if (io.lane == 0) ctl_write(ctl_land, landed);
+    ++retired;
+    if (retired == 1) io_mark(io, 9);
+  };
+  unsigned idle = 0;
+  while (issued < n_batches) {
+    const int i0 = issued * GB;
+    const int nv = nk - i0 < GB ? nk - i0 : GB;
+    // ring space: a slot is free once its wave has read the k-tile that was there RS before
+    bool room = (int)(a_seq + (unsigned)nv - done) <= RS;
+    if (!room) {
+      done = ctl_read(ctl_done);
+      room = (int)(a_seq + (unsigned)nv - done) <= RS;
+    }
+    if (!room || issued - retired == FL || (retired == 0 && issued == 1)) {  // (the first batch is waited for alone: the MFMA waves start on it)
+      if (issued > retired) {
+        retire_oldest();
+        continue;
+      }
+      __builtin_amdgcn_s_sleep(1);
+      if ((++idle & 255u) == 0 && (ctl_read(io.ctl + 4 * K_DEAD) != 0 || idle > SPIN_LDS)) {
+        ctl_write(io.ctl + 4 * K_DEAD, 1u);
+        io.ok = 0;
+        return false;
+      }
+      continue;
+    }
+    idle = 0;
+    const unsigned slot0 = a_seq & (unsigned)(RS - 1);
+    const unsigned so = (unsigned)(w + NW * i0) * (unsigned)(MT * 1024);
+    if (nv == GB && slot0 + GB <= (unsigned)RS) {
+      const unsigned dst = region + slot0 * (unsigned)(MT * 1024);
+#pragma unroll
+      for (int g = 0; g < GB; ++g) operand_ktile<MT>(ra, dst + (unsigned)(g * MT * 1024), voff, so + (unsigned)(g * NW * MT * 1024));
+    } else {
+#pragma unroll
+      for (int g = 0; g < GB; ++g) {  // (a missing k-tile is requested out of range, so every batch counts the same)
+        const unsigned dst = region + ((slot0 + (unsigned)g) & (unsigned)(RS - 1)) * (unsigned)(MT * 1024);
+        operand_ktile<MT>(ra, dst, g < nv ? voff : OOB, g < nv ? so + (unsigned)(g * NW * MT * 1024) : 0u);
+      }
+    }
+    a_seq += (unsigned)nv;
+    ++issued;
+  }
+  while (retired < issued) retire_oldest();
+  return true;
+}
+
 template <int MT, int NW>
 __device__ __forceinline__ bool load_operand(Io &io, const uint16_t *A, int KT, unsigned (&a_seq)[NW / (8 - NW)], int dbg) {
+  if constexpr (NW == 8 - NW) return load_operand_1<MT, NW>(io, A, KT, a_seq[0], dbg);
   constexpr int NIO = 8 - NW, SV = NW / NIO, RS = Lay<MT, NW>::RS, GB = 4, LPB = GB * SV * MT;
   constexpr int FL0 = RS / GB < 63 / LPB + 1 ? RS / GB : 63 / LPB + 1;  // batches in flight: (FL - 1) LPB loads must fit the counter
   constexpr int FL = FL0 < 8 ? FL0 : 8;
@@ -613,6 +737,7 @@ __device__ __forceinline__ bool load_operand(Io &io, const uint16_t *A, int KT, 
       }
     }
     ++retired;
+    if (retired == 1) io_mark(io, 9);
   };
   unsigned idle = 0;
   while (issued < n_batches) {
@@ -872,16 +997,18 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
 
 // One pass on the IO side: operand in, wait for the partial tiles, add them (wave 0, 1, ... in
 // that order), epilogue.
-template <int MT, int NW>
+template <int MT, int NW, typename Between>
 __device__ __forceinline__ bool io_pass(const StackArgs &a, Io &io, const Pass &p, unsigned pseq, const uint16_t *A, const float *rsq_in,
-                                        const Epi &q, int L, int x_lds, unsigned (&a_seq)[NW / (8 - NW)]) {
+                                        const Epi &q, int L, int x_lds, unsigned (&a_seq)[NW / (8 - NW)], Between between) {
   constexpr int NIO = 8 - NW, NT_IO = NIO * 64;
   const unsigned long long t_a = io.tr ? wall_clock64() : 0ull;
+  if (p.pidx == 0) io_mark(io, 10);
   RowStat<MT, NIO> rs;
   if (rsq_in) row_factors_load<MT, NIO>(io, rsq_in, a.Bp, a.ncg, rs);
   if (!load_operand<MT, NW>(io, A, p.KT, a_seq, LA_DBG_BITS(a.dbg))) return false;
   if (io.tr && io.v == 0 && io.lane == 0 && p.pidx == 0) io.tr[3] = wall_clock64() - t_a;  // (reported as "waited for weights": the operand's way in)
   if (rsq_in) row_factors_finish<MT, NIO>(io, a.Bp, a.inv_d, a.eps, rs);
+  between();  // (bookkeeping of the caller that needs no result of this pass: it runs while the MFMA waves finish)
   for (int w = 0; w < NW; ++w)
     if (!io_wait_ge(io, K_PDONE + w, pseq + 1u)) return false;
   if (p.pidx == 0) io_mark(io, 1);
@@ -1295,9 +1422,9 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
       q.mode = MODE_UNEMBED;
       q.un_part = a.un_part + (size_t)blockIdx.x * a.un_parts_per_cu * 64;
       q.part = pw.cur.pidx;
-      if (!io_pass<MT, NW>(a, io, pw.cur, pseq, a.xa, nullptr, q, L, 0, a_seq)) return;
+      const Pass cur = pw.cur;
+      if (!io_pass<MT, NW>(a, io, cur, pseq, a.xa, nullptr, q, L, 0, a_seq, [&]() { pw.next(); })) return;
       ++pseq;
-      pw.next();
     }
     if (!io_grid_sync<NIO>(a, io, ++epoch)) return;
     set_phase(2);
@@ -1374,9 +1501,10 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
           if (!io_barrier<NIO>(io)) return;
         }
         first = false;
-        if (!io_pass<MT, NW>(a, io, pw.cur, pseq, A, rsq_in, q, L, x_lds, a_seq)) return;
+        const Pass cur = pw.cur;
+        if (!io_pass<MT, NW>(a, io, cur, pseq, A, rsq_in, q, L, x_lds, a_seq, [&]() { pw.next(); })) return;
         ++pseq;
-        pw.next();
+        io_mark(io, 11);
       }
       if (gemm == 0)
         for (int u = att_u0; u < n_units; u += gridDim.x) r_kv_touch<NIO>(Kc, Vc, u, n_rt, a.Hkv, a.dh, L, io);  // (the first slice's workgroups)
