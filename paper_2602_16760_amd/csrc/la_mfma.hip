@@ -460,8 +460,10 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       const unsigned long long *mw = &h[(size_t)TRACE_SLOTS * f->trace_phases + TRACE_WG];
       const unsigned t0 = (unsigned)h[(size_t)TRACE_SLOTS * 6];  // (start of the second layer's first phase)
       for (int w = 0; w < 4; ++w) {
-        fprintf(stderr, "[la trace]   MFMA wave %d, second layer, start of its bodies, us after the layer's first phase began:", w);
-        for (int e = 0; e < 16; ++e) fprintf(stderr, " %.1f", (double)(int)((unsigned)mw[16 * w + e] - t0) * 0.01);
+        fprintf(stderr, "[la trace]   MFMA wave %d, second layer, start of its bodies, us after the layer's first phase began (of which waiting for operand):", w);
+        for (int e = 0; e < 16; ++e)
+          fprintf(stderr, " %.1f(%.1f)", (double)(short)(unsigned short)(((unsigned)mw[16 * w + e] & 0xffffu) - (t0 & 0xffffu)) * 0.01,
+                  (double)((unsigned)mw[16 * w + e] >> 16) * 0.01);
         fprintf(stderr, "\n");
       }
     }

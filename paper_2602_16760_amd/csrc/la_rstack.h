@@ -350,7 +350,7 @@ __device__ __forceinline__ unsigned m_wait_ge(unsigned ctl, int word, unsigned w
 template <int MT, int NW>
 __device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT][Geo<MT>::NTMAX], u32x4 rsrc, int lane, bool no_weights, unsigned mask,
                                           int lg, unsigned a_seq, unsigned ctl, unsigned region, int w, unsigned next_mask, unsigned next_frag,
-                                          unsigned next_stride, int next_lg, unsigned &seen) {
+                                          unsigned next_stride, int next_lg, unsigned &seen, bool timed, unsigned &op_wait) {
   constexpr int RS = Lay<MT, NW>::RS, AM = Geo<MT>::NTMAX - 1;
   constexpr int GQ = MT <= 3 ? 4 : 2;  // slots per operand fetch (GQ x MT fragments in registers)
   constexpr int NG = RING_D / GQ;
@@ -388,7 +388,11 @@ __device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT
   for (int q = 0; q < NG; ++q) {
     const unsigned need = (unsigned)__builtin_amdgcn_readlane((int)v_need, q);
     if (need != 0) {
-      if ((int)(seen - need) < 0) seen = m_wait_ge(ctl, K_ALAND + w, need);
+      if ((int)(seen - need) < 0) {
+        const unsigned long long t0 = timed ? wall_clock64() : 0ull;
+        seen = m_wait_ge(ctl, K_ALAND + w, need);
+        if (timed) op_wait += (unsigned)(wall_clock64() - t0);  // (timeline: how long this body waited for its operand)
+      }
 #pragma unroll
       for (int i = 0; i < GQ; ++i) {
         const unsigned ad = (unsigned)__builtin_amdgcn_readlane((int)v_a, GQ * q + i) + lane16;
@@ -495,10 +499,9 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
   for (int l = 0; l < n_layers; ++l) {
     const unsigned seg = seg_first + (unsigned)l * seg_stride;
     for (int e = 0; e < n_ent; ++e) {
-      if (LA_TRACE_PTR(a) && l == 1 && e < 16 && w < 4) {  // (timeline: when each of the first four MFMA waves starts each body of the second layer; low clock word)
-        const unsigned long long t = wall_clock64();
-        if (lane == 0) ctl_write(misc + M_BYTES + NW * TAB_BYTES + 4u * (unsigned)(16 * w + e), (unsigned)t);
-      }
+      const bool timed = LA_TRACE_PTR(a) && l == 1 && e < 16 && w < 4;  // (timeline: when each of the first four MFMA waves starts each body of the second layer)
+      const unsigned t_body = timed ? (unsigned)wall_clock64() : 0u;
+      unsigned op_wait = 0;
       const unsigned a_seq = (unsigned)l * a_per_layer + ent_word(e, 2);
       const unsigned w3 = ent_word(e, 3), w4 = ent_word(e, 4);
       const int lg = (int)((w3 >> 16) & 0xffu);
@@ -514,7 +517,9 @@ __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0
       const int nlg = (int)((nw3 >> 16) & 0xffu);
       const bool last = (w4 & 1u) != 0;
       const unsigned pseq = (unsigned)l * p_per_layer + (w4 >> 16);
-      mfma_body<MT, NW>(ring, acc, rsrc, lane, no_weights, uni(ent_word(e, 0)), lg, a_seq, ctl, region, w, nm, nf, nst, nlg, seen);
+      mfma_body<MT, NW>(ring, acc, rsrc, lane, no_weights, uni(ent_word(e, 0)), lg, a_seq, ctl, region, w, nm, nf, nst, nlg, seen, timed, op_wait);
+      // (low 16 bits of the clock at the body's start, and the time it waited for operand, in 10 ns)
+      if (timed && lane == 0) ctl_write(misc + M_BYTES + NW * TAB_BYTES + 4u * (unsigned)(16 * w + e), (t_body & 0xffffu) | ((op_wait > 0xffffu ? 0xffffu : op_wait) << 16));
       if (last) {
         // the pass is done for this wave: partial tile to LDS (its operand ring is idle now), tell the IO waves
         dump_partial<MT>(acc, lg, region, lane);
@@ -659,7 +664,7 @@ __device__ __forceinline__ bool load_operand_1(Io &io, const uint16_t *A, int KT
       done = ctl_read(ctl_done);
       room = (int)(a_seq + (unsigned)nv - done) <= RS;
     }
-    if (!room || issued - retired == FL || (retired == 0 && issued == 1)) {  // (the first batch is waited for alone: the MFMA waves start on it)
+    if (!room || issued - retired == FL) {  // (the first batches go out together: waiting for the first one alone cost 0.3 % at 32 rows and 1.7 % at one row)
       if (issued > retired) {
         retire_oldest();
         continue;
@@ -840,11 +845,36 @@ struct Epi {
   int part;
 };
 
+// The rotation factors of a thread's item of the QKV epilogue (16 floats: cos, sin of eight pairs), requested before
+// the wait for the partial tiles: they do not depend on the product, and read inside the epilogue their latency stood
+// between the reduction and the stores of every layer.  Covers the first item of each thread (there is no second one
+// unless a workgroup has more than 256 / rows column tiles in the pass; later items read theirs in place).
+struct QkvPre {
+  f32x4 c[4];
+  bool have;
+};
+template <int NIO>
+__device__ __forceinline__ void qkv_prefetch(const StackArgs &a, const Io &io, int tile_first, int ntc, QkvPre &pre) {
+  const int it = io.tid, dh = a.dh, half = dh >> 1, spj = dh >> 4;
+  pre.have = false;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pre.c[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (it >= a.Bp * ntc) return;
+  const int b = it / ntc, tt = it - b * ntc;
+  const int gt = (int)blockIdx.x + (int)gridDim.x * (tile_first + tt);
+  const int hs = gt / spj, j = gt - hs * spj;
+  if (hs >= a.Hq + a.Hkv) return;
+  const f32x4 *cp = reinterpret_cast<const f32x4 *>(a.cs + ((size_t)b * half + 8 * j) * 2);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) pre.c[i] = cp[i];
+  pre.have = true;
+}
+
 // The epilogue of a pass on the reduced tile (rows x NT column tiles, row-major [row][LDT] in the
 // first region), by all IO threads.  Same arithmetic as la_stack.h's gemm_epilogue.
 template <int MT, int NIO>
 __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, const Epi &q, int L, int x_lds, int tile_first, int ntc,
-                                              int LDT) {
+                                              int LDT, const QkvPre &pre) {
   constexpr int NT_IO = NIO * 64;
   const int Bp = a.Bp, d = a.d, ncg = a.ncg, Hq = a.Hq, Hkv = a.Hkv, dh = a.dh;
   const int tid = io.tid;
@@ -866,7 +896,14 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
       for (int k = 0; k < 8; ++k) {
         float x0 = tr[k] * rsf, x1 = tr[8 + k] * rsf;
         if (hs < Hq + Hkv) {
-          float c = cs[((size_t)b * half + 8 * j + k) * 2], sn = cs[((size_t)b * half + 8 * j + k) * 2 + 1];
+          float c, sn;
+          if (it == tid && pre.have) {
+            c = pre.c[k >> 1][(k & 1) * 2];
+            sn = pre.c[k >> 1][(k & 1) * 2 + 1];
+          } else {
+            c = cs[((size_t)b * half + 8 * j + k) * 2];
+            sn = cs[((size_t)b * half + 8 * j + k) * 2 + 1];
+          }
           y0[k] = (x0 * c - x1 * sn) * qscale;
           y1[k] = (x1 * c + x0 * sn) * qscale;
         } else {
@@ -1008,6 +1045,9 @@ __device__ __forceinline__ bool io_pass(const StackArgs &a, Io &io, const Pass &
   if (!load_operand<MT, NW>(io, A, p.KT, a_seq, LA_DBG_BITS(a.dbg))) return false;
   if (io.tr && io.v == 0 && io.lane == 0 && p.pidx == 0) io.tr[3] = wall_clock64() - t_a;  // (reported as "waited for weights": the operand's way in)
   if (rsq_in) row_factors_finish<MT, NIO>(io, a.Bp, a.inv_d, a.eps, rs);
+  QkvPre pre;
+  pre.have = false;
+  if (q.mode == MODE_QKV) qkv_prefetch<NIO>(a, io, p.tile0, p.NT, pre);
   between();  // (bookkeeping of the caller that needs no result of this pass: it runs while the MFMA waves finish)
   for (int w = 0; w < NW; ++w)
     if (!io_wait_ge(io, K_PDONE + w, pseq + 1u)) return false;
@@ -1026,7 +1066,7 @@ __device__ __forceinline__ bool io_pass(const StackArgs &a, Io &io, const Pass &
   }
   if (!io_barrier<NIO>(io)) return false;  // (also: the row factors, gains and x tiles other IO waves staged)
   if (p.pidx == 0) io_mark(io, 4);
-  pass_epilogue<MT, NIO>(a, io, q, L, x_lds, p.tile0, p.NT, LDT);
+  pass_epilogue<MT, NIO>(a, io, q, L, x_lds, p.tile0, p.NT, LDT, pre);
   if (p.pidx == 0) io_mark(io, 5);
   return true;
 }
@@ -1386,6 +1426,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
     ph = k;
     io.tr = (LA_TRACE_PTR(a) && blockIdx.x == 0 && k < a.trace_phases) ? LA_TRACE_PTR(a) + TRACE_SLOTS * k : nullptr;
     io_mark(io, 0);
+    if (io.tr && io.v == 0 && io.lane == 0) io.tr[12] = (unsigned long long)clock64();  // (shader clock, for its rate over the launch)
   };
   set_phase(0);
   unsigned epoch = a.epoch0;
