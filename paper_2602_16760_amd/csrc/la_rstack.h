@@ -1184,6 +1184,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
     // all units of a kv head run on one XCD and share its K, V lines in that XCD's L2 (r_kv_touch warms exactly those)
     const int rt = u / a.Hkv, kvh = u - rt * a.Hkv;
     const int b = (rt % MT) * 16 + c16;
+    io_mark(io, 10);  // (timeline of a unit: entry, late blocks done, early blocks done, merged, stored)
     const uint64_t vb = b < a.Bp ? a.vis[b] : 0ull;
     v8 q[KT];
 #pragma unroll
@@ -1275,6 +1276,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
       const v8 pb = softmax(std::true_type{}, sv, kb, corr);
       pv(pb, corr);
     }
+    io_mark(io, 9);
     if (e_lo + v < e_hi) {
       int kb = e_lo + v, ne = kb + NIO;
       float sv[8], corr;
@@ -1291,6 +1293,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
         ne += NIO;
       }
     }
+    io_mark(io, 1);
     // merge: waves 1 .. NIO-1 leave (o, m, l) in LDS, wave 0 adds them in wave order
     const unsigned qs = att_seq;
     if (v > 0) {
@@ -1316,6 +1319,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
         for (int dt = 0; dt < DT; ++dt) o[dt] = o[dt] * ca + red[dt * 64 + lane] * cb;
         m_run = m_new;
       }
+      io_mark(io, 4);
       bool writer = true;
       if (S > 1) {
         __amdgpu_buffer_rsrc_t rp = rsrc_of(a.att_part);
@@ -1359,6 +1363,7 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
                u32x2{pack_f16(o[dt][0] * inv, o[dt][1] * inv), pack_f16(o[dt][2] * inv, o[dt][3] * inv)});
         }
       }
+      io_mark(io, 5);
       __atomic_signal_fence(__ATOMIC_SEQ_CST);
       if (lane == 0) ctl_write(io.ctl + 4 * (K_ATT + 0), qs + 1u);
     }
@@ -1485,7 +1490,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
     while (S < 8 && n_units * 2 * S <= (int)gridDim.x && nkb >= 16 * 2 * S) S *= 2;
   }
   const int n_su = n_units * S;
-  const int att_first = att_first_wg(a.qkv.ntiles, n_su);
+  const int att_first = (LA_DBG_BITS(a.dbg) & 32) ? 0 : att_first_wg(a.qkv.ntiles, n_su);  // (timing experiment: the traced workgroup runs a unit)
   const int att_u0 = (int)blockIdx.x >= att_first ? (int)blockIdx.x - att_first : n_su;
   if (blockIdx.x == 0)  // the delivery counters start every launch at zero (visible after the first grid barrier)
     for (int i = io.tid; i < n_units; i += NIO * 64) __builtin_amdgcn_raw_buffer_store_b32(0u, rsrc_of(a.att_cnt), (unsigned)i * 4u, 0, DEV);
