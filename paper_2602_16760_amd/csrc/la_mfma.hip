@@ -520,13 +520,16 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     for (int k = 0; k < 8 && a.trace_sel + k < np - 1; ++k) {
       const size_t base = (size_t)TRACE_SLOTS * f->trace_phases + 8 + k;
       unsigned long long lo = ~0ull, hi = 0;
+      auto counted = [&](int g) { return !(f->use_r && (g == 1 || g == 2)); };  // (their words hold the MFMA waves' timeline)
       for (int g = 0; g < f->n_wgs; ++g) {
+        if (!counted(g)) continue;
         lo = std::min(lo, h[base + (size_t)TRACE_WG * g]);
         hi = std::max(hi, h[base + (size_t)TRACE_WG * g]);
       }
       double mean = 0, xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0}, half[2] = {0, 0};
       int nx[8] = {0, 0, 0, 0, 0, 0, 0, 0}, nh[2] = {0, 0};
       for (int g = 0; g < f->n_wgs; ++g) {
+        if (!counted(g)) continue;
         double t = (h[base + (size_t)TRACE_WG * g] - lo) * 0.01;
         mean += t / f->n_wgs;
         xcd[g % 8] += t; ++nx[g % 8];
@@ -539,7 +542,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
       if (env_int("LA_TRACE", 0) > 1) {  // every workgroup, one line per (workgroup % 8)
         for (int x = 0; x < 8; ++x) {
           fprintf(stderr, "[la trace]     %d:", x);
-          for (int g = x; g < f->n_wgs; g += 8) fprintf(stderr, " %.1f", (h[base + (size_t)TRACE_WG * g] - lo) * 0.01);
+          for (int g = x; g < f->n_wgs; g += 8) fprintf(stderr, " %.1f", counted(g) ? (h[base + (size_t)TRACE_WG * g] - lo) * 0.01 : -1.0);
           fprintf(stderr, "\n");
         }
       }

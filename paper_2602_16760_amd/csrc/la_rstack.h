@@ -546,6 +546,7 @@ struct Io {
   unsigned bar_seq;
   int ok;
   unsigned long long *tr;  // timeline slots of the running phase (workgroup 0, IO wave 0, lane 0) or null
+  int ph;                  // phase number (timeline)
 };
 __device__ __forceinline__ void io_mark(const Io &io, int k) {
   if (io.tr && io.v == 0 && io.lane == 0) io.tr[k] = wall_clock64();
@@ -577,6 +578,10 @@ template <int NIO>
 __device__ __forceinline__ bool io_grid_sync(const StackArgs &a, Io &io, unsigned epoch) {
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
   io_mark(io, 2);
+  if (LA_TRACE_PTR(a) && io.v == 0 && io.lane == 0 && (blockIdx.x == 0 || blockIdx.x > 2)) {  // (timeline: when each workgroup ends a phase)
+    const int k = io.ph - a.trace_sel;
+    if (k >= 0 && k < 8) LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG * blockIdx.x + 8 + k] = wall_clock64();
+  }
   wait_vmcnt<0>();  // this wave's stores are acknowledged
   io_mark(io, 6);
   if (!io_barrier<NIO>(io)) return false;
@@ -870,8 +875,33 @@ __device__ __forceinline__ void qkv_prefetch(const StackArgs &a, const Io &io, i
   pre.have = true;
 }
 
-// The epilogue of a pass on the reduced tile (rows x NT column tiles, row-major [row][LDT] in the
-// first region), by all IO threads.  Same arithmetic as la_stack.h's gemm_epilogue.
+// Eight consecutive floats (two one, for the arg-max scan) of the pass's tile: the MFMA waves' partial tiles, at the
+// same place in each wave's region, added in wave order.
+template <int NW, int REG>
+__device__ __forceinline__ void tile8(unsigned lds0, unsigned byte_off, float (&out)[8]) {
+  f32x4 s0 = *(LDS_AS const f32x4 *)(uintptr_t)(lds0 + byte_off), s1 = *(LDS_AS const f32x4 *)(uintptr_t)(lds0 + byte_off + 16u);
+#pragma unroll
+  for (int w = 1; w < NW; ++w) {
+    s0 += *(LDS_AS const f32x4 *)(uintptr_t)(lds0 + (unsigned)(w * REG) + byte_off);
+    s1 += *(LDS_AS const f32x4 *)(uintptr_t)(lds0 + (unsigned)(w * REG) + byte_off + 16u);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[i] = s0[i];
+    out[4 + i] = s1[i];
+  }
+}
+template <int NW, int REG>
+__device__ __forceinline__ float tile1(unsigned lds0, unsigned byte_off) {
+  float s = *(LDS_AS const float *)(uintptr_t)(lds0 + byte_off);
+#pragma unroll
+  for (int w = 1; w < NW; ++w) s += *(LDS_AS const float *)(uintptr_t)(lds0 + (unsigned)(w * REG) + byte_off);
+  return s;
+}
+
+// The epilogue of a pass (rows x NT column tiles; every MFMA wave's partial tile row-major [row][LDT] at the start of
+// its region), by all IO threads: each thread adds the partial tiles of the elements it works on (a pass over the whole
+// tile first, with a barrier behind it, took 0.5 - 1 us more per phase).  Same arithmetic as la_stack.h's gemm_epilogue.
 template <int MT, int NIO>
 __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, const Epi &q, int L, int x_lds, int tile_first, int ntc,
                                               int LDT, const QkvPre &pre) {
@@ -879,7 +909,7 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
   const int Bp = a.Bp, d = a.d, ncg = a.ncg, Hq = a.Hq, Hkv = a.Hkv, dh = a.dh;
   const int tid = io.tid;
   const float *cs = a.cs;
-  LDS_AS const float *tile = (LDS_AS const float *)(uintptr_t)io.lds0;
+  constexpr int NW = 8 - NIO, REG = Lay<MT, 8 - NIO>::REG;
   LDS_AS const float *rs_lds = (LDS_AS const float *)(uintptr_t)(io.misc + M_RS);
   const int G = gridDim.x, cu = blockIdx.x;
   if (q.mode == MODE_QKV) {
@@ -889,7 +919,17 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
       const int half = dh >> 1, spj = dh >> 4, grp = Hq / Hkv;
       const int hs = gt / spj, j = gt - hs * spj;
       const float rsf = rs_lds[b];
-      LDS_AS const float *tr = tile + b * LDT + 16 * tt;
+      float tr[16];
+      {
+        float lo8[8], hi8[8];
+        tile8<NW, REG>(io.lds0, (unsigned)(b * LDT + 16 * tt) * 4u, lo8);
+        tile8<NW, REG>(io.lds0, (unsigned)(b * LDT + 16 * tt + 8) * 4u, hi8);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          tr[k] = lo8[k];
+          tr[8 + k] = hi8[k];
+        }
+      }
       const float qscale = hs < Hq ? 1.0f / sqrtf((float)dh) : 1.0f;
       float y0[8], y1[8];
 #pragma unroll
@@ -943,7 +983,8 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
       const int gt = cu + G * (tile_first + tt);
       const int col = 16 * gt + 8 * oct;
       f32x4 *xp = reinterpret_cast<f32x4 *>(a.x + (size_t)b * d + col);
-      LDS_AS const float *tr = tile + b * LDT + 16 * tt + 8 * oct;
+      float tr[8];
+      tile8<NW, REG>(io.lds0, (unsigned)(b * LDT + 16 * tt + 8 * oct) * 4u, tr);
       LDS_AS f32x4 *xs = (LDS_AS f32x4 *)(uintptr_t)(io.misc + M_X + (((tile_first + tt) * 16 * MT + b) * 16 + 8 * oct) * 4);
       f32x4 x0, x1;
       if (x_lds) {
@@ -994,7 +1035,9 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
       const int b = it / ntc, tt = it - b * ntc;
       const int gt = cu + G * (tile_first + tt);
       const float rsf = rs_lds[b];
-      LDS_AS const float *gp = tile + b * LDT + 16 * tt, *up = gp + 8;
+      float gp[8], up[8];
+      tile8<NW, REG>(io.lds0, (unsigned)(b * LDT + 16 * tt) * 4u, gp);
+      tile8<NW, REG>(io.lds0, (unsigned)(b * LDT + 16 * tt + 8) * 4u, up);
       float act[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -1011,7 +1054,7 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
       if (row < Bp)
         for (int c = j; c < 16 * ntc; c += 4) {
           int gt = cu + G * (tile_first + (c >> 4));
-          best = top_merge2(best, Top{tile[row * LDT + c], 16 * gt + (c & 15), -INFINITY});
+          best = top_merge2(best, Top{tile1<NW, REG>(io.lds0, (unsigned)(row * LDT + c) * 4u), 16 * gt + (c & 15), -INFINITY});
         }
 #pragma unroll
       for (int o = 1; o < 4; o <<= 1) {
@@ -1049,22 +1092,12 @@ __device__ __forceinline__ bool io_pass(const StackArgs &a, Io &io, const Pass &
   pre.have = false;
   if (q.mode == MODE_QKV) qkv_prefetch<NIO>(a, io, p.tile0, p.NT, pre);
   between();  // (bookkeeping of the caller that needs no result of this pass: it runs while the MFMA waves finish)
+  if (!io_barrier<NIO>(io)) return false;  // (the row factors, gains and x tiles the IO waves staged for each other)
   for (int w = 0; w < NW; ++w)
     if (!io_wait_ge(io, K_PDONE + w, pseq + 1u)) return false;
   if (p.pidx == 0) io_mark(io, 1);
   __atomic_signal_fence(__ATOMIC_SEQ_CST);
   const int LDT = 16 * p.NTS + 4;
-  {
-    const int n4 = 16 * MT * LDT / 4;
-    LDS_AS f32x4 *t0 = (LDS_AS f32x4 *)(uintptr_t)io.lds0;
-    for (int i = io.tid; i < n4; i += NT_IO) {
-      f32x4 s = t0[i];
-#pragma unroll
-      for (int w = 1; w < NW; ++w) s += *(LDS_AS const f32x4 *)(uintptr_t)(io.lds0 + (unsigned)w * Lay<MT, NW>::REG + (unsigned)i * 16u);
-      t0[i] = s;
-    }
-  }
-  if (!io_barrier<NIO>(io)) return false;  // (also: the row factors, gains and x tiles other IO waves staged)
   if (p.pidx == 0) io_mark(io, 4);
   pass_epilogue<MT, NIO>(a, io, q, L, x_lds, p.tile0, p.NT, LDT, pre);
   if (p.pidx == 0) io_mark(io, 5);
@@ -1426,9 +1459,11 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
   io.v = v; io.lane = lane; io.tid = v * 64 + lane;
   io.bar_seq = 0; io.ok = 1;
   io.tr = nullptr;
+  io.ph = 0;
   int ph = 0;  // phase number as in la_stack.h: first operand, then five per layer
   auto set_phase = [&](int k) {
     ph = k;
+    io.ph = k;
     io.tr = (LA_TRACE_PTR(a) && blockIdx.x == 0 && k < a.trace_phases) ? LA_TRACE_PTR(a) + TRACE_SLOTS * k : nullptr;
     io_mark(io, 0);
     if (io.tr && io.v == 0 && io.lane == 0) io.tr[12] = (unsigned long long)clock64();  // (shader clock, for its rate over the launch)
