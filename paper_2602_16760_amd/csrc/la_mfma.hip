@@ -250,8 +250,8 @@ int mfma_create(la_model *m) {
   f->p_down = make_plan(d.d_model, d.d_ffn, f->n_wgs);
   f->p_un = make_plan(d.vocab, d.d_model, f->n_wgs);
   if (f->use_r)  // the MFMA waves' schedule tables hold a fixed number of entries per layer (and for the unembedding)
-    for (int ntmax : {rs::Geo<1>::NTMAX, rs::Geo<4>::NTMAX}) {
-      auto nb = [&](const GemmPlan &p) { return rs::schedule_bodies(p.KT, p.nt_max, p.ntp, ntmax, R_NW); };
+    for (int ring : {rs::Geo<2>::RING, rs::Geo<3>::RING, rs::Geo<4>::RING}) {
+      auto nb = [&](const GemmPlan &p) { return rs::schedule_bodies(p.KT, p.nt_max, p.ntp, rs::Geo<1>::NTMAX, ring, R_NW); };
       const int layer = nb(f->p_qkv) + nb(f->p_o) + nb(f->p_gu) + nb(f->p_down), un = nb(f->p_un);
       LA_REQUIRE(layer <= rs::TAB_MAX && un <= rs::TAB_MAX, LA_EINVAL,
                  "the register-streaming kernel's schedule has %d entries per layer and %d for the unembedding; it holds %d (LA_LDS_RING=1 "

@@ -41,11 +41,15 @@
 namespace la {
 namespace rs {
 
-constexpr int RING_D = 32;  // weight fragments per MFMA wave in flight or landed (4 VGPRs each)
+constexpr int RING_MAX = 32;  // most weight fragments per MFMA wave in flight or landed (4 VGPRs each; Geo<MT>::RING)
 
 template <int MT>
 struct Geo {
-  static constexpr int NTMAX = MT <= 2 ? 8 : 4;                       // column tiles per pass
+  static constexpr int NTMAX = 8;                                     // column tiles per pass
+  // Weight fragments per MFMA wave in flight or landed.  Up to 32 rows a wave's registers hold 32 of them beside the
+  // accumulators of eight column tiles; with 48 and 64 rows they hold 24 and 16 (the depth matters little: 16 instead
+  // of 32 cost 0.9 % at 32 rows), so that gate/up (seven tiles per workgroup at the 7B shape) stays one pass.
+  static constexpr int RING = MT <= 2 ? 32 : MT == 3 ? 24 : 16;
   static constexpr int LDTMAX = 16 * NTMAX + 4;                       // padded row length of a partial tile (floats)
   static constexpr int PART_BYTES = 16 * MT * LDTMAX * 4;             // one wave's partial tile
 };
@@ -93,7 +97,7 @@ struct Pass {
 
 __device__ __forceinline__ int slots_for(int nt) { return nt <= 1 ? 1 : nt <= 2 ? 2 : nt <= 4 ? 4 : 8; }
 // k-tiles of one body of a pass with NTS slots per k-tile
-__device__ __forceinline__ int body_rows(int NTS) { return RING_D / NTS; }
+__device__ __forceinline__ int body_rows(int NTS, int ring) { return ring / NTS; }
 
 // Walks the passes of a launch in order (uniform values only; plain integers, picked by
 // comparisons: an indexed array or a selected struct would live in scratch memory, and an MFMA
@@ -193,14 +197,14 @@ __device__ __forceinline__ void ring_wait(u32x4 &slot) {
 template <int NW>
 struct BodyCursor {
   PassWalk pw;
-  int w;
+  int w, ring;         // MFMA wave; slots per body
   int nk, i0;          // this wave's k-tiles of the current pass; first k-tile (of its own) of the current body
   unsigned frag0;      // stream fragment index of (this wave's first k-tile, the pass's first tile)
   unsigned a_seq0;     // operand k-tiles of this wave before the current pass
   unsigned pseq;       // passes before the current one
-  __device__ __forceinline__ void init(const StackArgs &a, int ntmax, int w_, bool one_layer = false) {
+  __device__ __forceinline__ void init(const StackArgs &a, int ntmax, int ring_, int w_, bool one_layer = false) {
     pw.init(a, ntmax, one_layer);
-    w = w_; a_seq0 = 0; pseq = 0;
+    w = w_; ring = ring_; a_seq0 = 0; pseq = 0;
     enter();
   }
   __device__ __forceinline__ void enter() {
@@ -221,7 +225,7 @@ struct BodyCursor {
   // real slots of the current body: slot j <-> (k-tile i0 + j / NTS, tile j % NTS)
   __device__ __forceinline__ unsigned mask() const {
     if (pw.done) return 0u;
-    const int NTS = pw.cur.NTS, DK = body_rows(NTS);
+    const int NTS = pw.cur.NTS, DK = body_rows(NTS, ring);
     const int left = nk - i0;
     const int rows = left < DK ? (left > 0 ? left : 0) : DK;
     const unsigned rowmask = (1u << pw.cur.NT) - 1u;
@@ -230,7 +234,7 @@ struct BodyCursor {
     return m;
   }
   __device__ __forceinline__ void next_body() {  // (only while !pass_finished())
-    i0 += body_rows(pw.cur.NTS);
+    i0 += body_rows(pw.cur.NTS, ring);
   }
   __device__ __forceinline__ void next_pass() {
     a_seq0 += (unsigned)nk;
@@ -262,24 +266,24 @@ constexpr int TAB_BYTES = TAB_HDR + TAB_MAX * 20;
 
 // Host: bodies of one GEMM in an MFMA wave's schedule, at most (the workgroup with the most column tiles, the wave
 // with the most k-tiles), for passes of up to ntmax tiles.  The tables hold TAB_MAX bodies per layer.
-inline int schedule_bodies(int KT, int nt_max, int ntp, int ntmax, int NW) {
+inline int schedule_bodies(int KT, int nt_max, int ntp, int ntmax, int ring, int NW) {
   const int step = ntp < ntmax ? ntp : ntmax;
   const int nk = (KT + NW - 1) / NW;
   int n = 0;
   for (int t0 = 0; t0 < nt_max; t0 += step) {
     const int NT = nt_max - t0 < step ? nt_max - t0 : step;
     const int NTS = NT <= 1 ? 1 : NT <= 2 ? 2 : NT <= 4 ? 4 : 8;
-    const int b = (nk * NTS + RING_D - 1) / RING_D;
+    const int b = (nk * NTS + ring - 1) / ring;
     n += b > 1 ? b : 1;
   }
   return n;
 }
 
 template <int NW>
-__device__ __forceinline__ void build_schedule(const StackArgs &a, int ntmax, int w, unsigned tab) {
+__device__ __forceinline__ void build_schedule(const StackArgs &a, int ntmax, int ring, int w, unsigned tab) {
   // one layer's worth: layers lb .. lb + 1 of a stack launch, or the unembedding
   BodyCursor<NW> c;
-  c.init(a, ntmax, w, true);
+  c.init(a, ntmax, ring, w, true);
   const unsigned seg0 = a.mode == 0 ? (unsigned)a.lb * a.seg_frags : 0u;
   LDS_AS unsigned *hdr = (LDS_AS unsigned *)(uintptr_t)tab;
   int n = 0;
@@ -295,7 +299,7 @@ __device__ __forceinline__ void build_schedule(const StackArgs &a, int ntmax, in
       c.next_pass();
       continue;
     }
-    const int DK = body_rows(c.pw.cur.NTS);
+    const int DK = body_rows(c.pw.cur.NTS, ring);
     const int rows = c.nk - c.i0 < DK ? c.nk - c.i0 : DK;
     const bool last = c.i0 + DK >= c.nk;
     if (n < TAB_MAX) {
@@ -348,13 +352,14 @@ __device__ __forceinline__ unsigned m_wait_ge(unsigned ctl, int word, unsigned w
 // landing count it needs and which count it acknowledges); a slot then takes its values out of
 // these vectors with one v_readlane each.
 template <int MT, int NW>
-__device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT][Geo<MT>::NTMAX], u32x4 rsrc, int lane, bool no_weights, unsigned mask,
+__device__ __forceinline__ void mfma_body(u32x4 (&ring)[Geo<MT>::RING], f32x4 (&acc)[MT][Geo<MT>::NTMAX], u32x4 rsrc, int lane, bool no_weights, unsigned mask,
                                           int lg, unsigned a_seq, unsigned ctl, unsigned region, int w, unsigned next_mask, unsigned next_frag,
                                           unsigned next_stride, int next_lg, unsigned &seen, bool timed, unsigned &op_wait) {
   constexpr int RS = Lay<MT, NW>::RS, AM = Geo<MT>::NTMAX - 1;
-  constexpr int GQ = MT <= 3 ? 4 : 2;  // slots per operand fetch (GQ x MT fragments in registers)
-  constexpr int NG = RING_D / GQ;
-  static_assert((RS & (RS - 1)) == 0 && RING_D == 32, "ring slot by masking; one slot per lane of a half wave");
+  constexpr int GQ = MT <= 2 ? 4 : 2;  // slots per operand fetch (GQ x MT fragments in registers)
+  constexpr int RING_D = Geo<MT>::RING, NG = RING_D / GQ;
+  static_assert((RS & (RS - 1)) == 0 && RING_D <= RING_MAX && RING_D % GQ == 0 && RING_D % Geo<MT>::NTMAX == 0,
+                "ring slot by masking; one slot per lane of a half wave; whole groups and whole k-tiles per body");
   const unsigned lane16 = (unsigned)lane * 16u;
   // -- per slot (lane j) --
   const unsigned j_l = (unsigned)lane & 31u;
@@ -366,7 +371,7 @@ __device__ __forceinline__ void mfma_body(u32x4 (&ring)[RING_D], f32x4 (&acc)[MT
   // LDS address of the slot's operand k-tile
   const unsigned v_a = region + ((a_seq + (j_l >> lg)) & (unsigned)(RS - 1)) * (unsigned)(MT * 1024);
   // -- per group (lane q) --
-  const unsigned q_l = (unsigned)lane & (unsigned)(NG - 1);
+  const unsigned q_l = ((unsigned)lane & 31u) < (unsigned)NG ? ((unsigned)lane & 31u) : 0u;  // (lanes beyond the groups are never read)
   const unsigned g0 = (unsigned)GQ * q_l;
   const unsigned qm_l = (mask >> g0) & ((1u << GQ) - 1u);
   // (a group that lies inside the k-tile of the group before it keeps that group's fragments)
@@ -456,7 +461,7 @@ __device__ __forceinline__ void dump_partial(const f32x4 (&acc)[MT][Geo<MT>::NTM
 
 template <int MT, int NW>
 __device__ __forceinline__ void mfma_wave_main(const StackArgs &a, unsigned lds0, int w, int lane) {
-  constexpr int NTMAX = Geo<MT>::NTMAX;
+  constexpr int NTMAX = Geo<MT>::NTMAX, RING_D = Geo<MT>::RING;
   const unsigned misc = lds0 + NW * Lay<MT, NW>::REG;
   const unsigned ctl = misc + M_CTL;
   const unsigned tab = misc + M_BYTES + (unsigned)w * TAB_BYTES;
@@ -1609,7 +1614,7 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
   const unsigned lds0 = (unsigned)(uintptr_t)lds;
   // (the schedules are written by threads of the last wave: an IO wave, whose use of scratch memory is harmless)
   if (threadIdx.x >= WG_THREADS - NW)
-    build_schedule<NW>(a, Geo<MT>::NTMAX, (int)threadIdx.x - (WG_THREADS - NW),
+    build_schedule<NW>(a, Geo<MT>::NTMAX, Geo<MT>::RING, (int)threadIdx.x - (WG_THREADS - NW),
                        lds0 + NW * Lay<MT, NW>::REG + M_BYTES + (threadIdx.x - (WG_THREADS - NW)) * TAB_BYTES);
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
   if (LA_TRACE_PTR(a) && blockIdx.x == 0 && threadIdx.x == 0) LA_TRACE_PTR(a)[14] = wall_clock64();  // (timeline: schedules written)
