@@ -160,6 +160,7 @@ struct MfmaModel {
   float *att_part = nullptr;    // attention with the keys split over workgroups: one partial record per workgroup
   unsigned *att_cnt = nullptr;  // ... and per unit the number of records delivered
   unsigned *sync = nullptr;
+  unsigned *sched[3][2] = {};  // register-streaming kernel: schedule tables per ring depth (32, 24, 16 slots) and mode (stack, unembedding)
   int32_t *zero_len = nullptr;  // a cache length of 0: the unembedding has no cache to overflow
   unsigned epoch = 0;
   unsigned long long *trace = nullptr;  // LA_TRACE=1: per-phase timestamps, printed after each launch
@@ -204,6 +205,7 @@ void mfma_destroy(la_model *m) {
   if (!f) return;
   void *ps[] = {f->wstream, f->ustream, f->xa, f->attn_a, f->act_a, f->qf, f->xa_u, f->rsq_u, f->rsq, f->un_part,
                 f->sync, f->dev_gains, f->zero_len, f->trace, f->att_part, f->att_cnt,
+                f->sched[0][0], f->sched[0][1], f->sched[1][0], f->sched[1][1], f->sched[2][0], f->sched[2][1],
                 f->pf.x, f->pf.rs, f->pf.cs, f->pf.A, f->pf.Q, f->pf.attn, f->pf.act};
   for (void *p : ps)
     if (p) (void)hipFree(p);
@@ -218,6 +220,7 @@ void mfma_reset_sync(la_model *m, hipStream_t s) {
 }
 
 static int na_setup(int device);  // address of the static scratch array on this device (defined with its entry point below)
+static GemmDev dev_plan(const GemmPlan &p);
 
 int mfma_create(la_model *m) {
   const la_model_desc &d = m->d;
@@ -293,6 +296,28 @@ int mfma_create(la_model *m) {
   LA_HIP(hipMemset(f->qf, 0, (size_t)d.n_kv_heads * QR * d.head_dim * 2));
   LA_HIP(hipMemset(f->sync, 0, (size_t)n_sync * 4));
   LA_HIP(hipMemset(f->zero_len, 0, 8));
+  if (f->use_r) {  // the MFMA waves' schedules, once per model: per ring depth (row-tile counts 1-2, 3, 4) and mode
+    const int rings[3] = {rs::Geo<2>::RING, rs::Geo<3>::RING, rs::Geo<4>::RING};
+    const size_t bytes = (size_t)f->n_wgs * R_NW * rs::TAB_BYTES;
+    for (int c = 0; c < 3; ++c)
+      for (int mode = 0; mode < 2; ++mode) {
+        f->sched[c][mode] = (unsigned *)dalloc(bytes);
+        LA_REQUIRE(f->sched[c][mode] != nullptr, LA_ENOMEM, "device allocation failed in the MFMA path");
+        StackArgs a{};
+        a.mode = mode;
+        a.lb = 0;
+        a.le = 1;
+        a.qkv = dev_plan(f->p_qkv);
+        a.o = dev_plan(f->p_o);
+        a.gu = dev_plan(f->p_gu);
+        a.down = dev_plan(f->p_down);
+        a.un = dev_plan(f->p_un);
+        a.seg_frags = mode == 0 ? f->seg_frags : (unsigned)(f->ucu_bytes / 1024);
+        int rc = rs::write_schedule_tables<R_NW>(a, rings[c], f->sched[c][mode], f->n_wgs, nullptr);
+        if (rc) return rc;
+      }
+    LA_HIP(hipDeviceSynchronize());
+  }
 #ifdef LA_EXPERIMENTS
   if (env_int("LA_TRACE", 0)) {
     f->trace_phases = 2 + 5 * d.n_layers;
@@ -388,6 +413,7 @@ static int launch_stack(const char *name, MfmaModel *f, StackArgs a, int n_barri
     f->epoch += (unsigned)n_barriers;
   }
   a.n_groups = (unsigned)ceil_div(f->n_wgs, SYNC_GROUP);
+  a.sched = f->sched[a.MT <= 2 ? 0 : a.MT == 3 ? 1 : 2][a.mode];
   a.trace = fresh_sync ? nullptr : f->trace;
   a.trace_phases = f->trace_phases;
   a.trace_sel = env_int("LA_TRACE_SEL", 6);

@@ -1612,10 +1612,16 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
   }
   if (threadIdx.x < 64) ((LDS_AS unsigned *)(lds + NW * Lay<MT, NW>::REG + M_CTL))[threadIdx.x] = 0u;
   const unsigned lds0 = (unsigned)(uintptr_t)lds;
-  // (the schedules are written by threads of the last wave: an IO wave, whose use of scratch memory is harmless)
-  if (threadIdx.x >= WG_THREADS - NW)
-    build_schedule<NW>(a, Geo<MT>::NTMAX, Geo<MT>::RING, (int)threadIdx.x - (WG_THREADS - NW),
-                       lds0 + NW * Lay<MT, NW>::REG + M_BYTES + (threadIdx.x - (WG_THREADS - NW)) * TAB_BYTES);
+  // The MFMA waves' schedules: the same for every launch of a model with this row-tile count, so they are worked out
+  // once, when the model is created (schedule_tables_kernel), and every launch copies its workgroup's tables into LDS
+  // (built here by one thread per MFMA wave they took 10 - 15 us at the start of every launch).
+  {
+    constexpr int N16 = NW * TAB_BYTES / 16;
+    static_assert(NW * TAB_BYTES % 16 == 0, "whole 16-byte pieces");
+    const u32x4 *src = reinterpret_cast<const u32x4 *>(a.sched) + (size_t)blockIdx.x * N16;
+    LDS_AS u32x4 *dst = (LDS_AS u32x4 *)(lds + NW * Lay<MT, NW>::REG + M_BYTES);
+    for (int i = threadIdx.x; i < N16; i += WG_THREADS) dst[i] = src[i];
+  }
   __syncthreads();  // the only hardware barrier: from here on the waves run decoupled
   if (LA_TRACE_PTR(a) && blockIdx.x == 0 && threadIdx.x == 0) LA_TRACE_PTR(a)[14] = wall_clock64();  // (timeline: schedules written)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1637,6 +1643,28 @@ __global__ __launch_bounds__(WG_THREADS) void rstack_kernel(StackArgs a) {
       LA_TRACE_PTR(a)[(size_t)TRACE_SLOTS * a.trace_phases + TRACE_WG + lane] = v;  // (the words of workgroups 1 and 2, which leave theirs alone)
     }
   }
+}
+
+// Writes the schedule tables of every workgroup of a launch shape (a.mode, the plans and a.seg_frags; ring slots per
+// body as for the row-tile count that will use them) into out[workgroup][MFMA wave][TAB_BYTES].  Launched with the grid
+// of the persistent kernel (the tables depend on the workgroup's index and the grid's size) and NW threads.
+template <int NW>
+__global__ void schedule_tables_kernel(StackArgs a, int ntmax, int ring, unsigned *out) {
+  __shared__ __attribute__((aligned(16))) uint8_t tabs[NW * TAB_BYTES];
+  const unsigned base = (unsigned)(uintptr_t)(lds_t)tabs;
+  if (threadIdx.x < NW) {
+    LDS_AS unsigned *mine = (LDS_AS unsigned *)(uintptr_t)(base + threadIdx.x * TAB_BYTES);
+    for (int i = 0; i < TAB_BYTES / 4; ++i) mine[i] = 0u;
+    build_schedule<NW>(a, ntmax, ring, (int)threadIdx.x, base + threadIdx.x * TAB_BYTES);
+    unsigned *dst = out + ((size_t)blockIdx.x * NW + threadIdx.x) * (TAB_BYTES / 4);
+    for (int i = 0; i < TAB_BYTES / 4; ++i) dst[i] = mine[i];
+  }
+}
+template <int NW>
+int write_schedule_tables(const StackArgs &a, int ring, unsigned *out, int n_wgs, hipStream_t s) {
+  schedule_tables_kernel<NW><<<n_wgs, 64, 0, s>>>(a, Geo<1>::NTMAX, ring, out);
+  LA_HIP(hipGetLastError());
+  return LA_OK;
 }
 
 // Run once per model: raises the kernel's LDS limit and checks that n_wgs workgroups can be resident at once on `cus`

@@ -179,6 +179,7 @@ struct StackArgs {
   int32_t *ids;
   float *top2;
   unsigned *sync;
+  const unsigned *sched;  // register-streaming kernel: the MFMA waves' schedule tables of every workgroup (written once per model)
   unsigned epoch0, n_groups;
   unsigned long long *trace;  // optional: per phase TRACE_SLOTS timestamps of workgroup 0, then TRACE_WG words per workgroup
   int trace_phases;
