@@ -880,7 +880,7 @@ __device__ __forceinline__ void qkv_prefetch(const StackArgs &a, const Io &io, i
   pre.have = true;
 }
 
-// Eight consecutive floats (two one, for the arg-max scan) of the pass's tile: the MFMA waves' partial tiles, at the
+// Eight consecutive floats of the pass's tile: the MFMA waves' partial tiles, at the
 // same place in each wave's region, added in wave order.
 template <int NW, int REG>
 __device__ __forceinline__ void tile8(unsigned lds0, unsigned byte_off, float (&out)[8]) {
@@ -896,14 +896,6 @@ __device__ __forceinline__ void tile8(unsigned lds0, unsigned byte_off, float (&
     out[4 + i] = s1[i];
   }
 }
-template <int NW, int REG>
-__device__ __forceinline__ float tile1(unsigned lds0, unsigned byte_off) {
-  float s = *(LDS_AS const float *)(uintptr_t)(lds0 + byte_off);
-#pragma unroll
-  for (int w = 1; w < NW; ++w) s += *(LDS_AS const float *)(uintptr_t)(lds0 + (unsigned)(w * REG) + byte_off);
-  return s;
-}
-
 // The epilogue of a pass (rows x NT column tiles; every MFMA wave's partial tile row-major [row][LDT] at the start of
 // its region), by all IO threads: each thread adds the partial tiles of the elements it works on (a pass over the whole
 // tile first, with a barrier behind it, took 0.5 - 1 us more per phase).  Same arithmetic as la_stack.h's gemm_epilogue.
@@ -1057,9 +1049,12 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
       const int row = r0 + (tid >> 2), j = tid & 3;
       Top best{-INFINITY, 0x7fffffff, -INFINITY};
       if (row < Bp)
-        for (int c = j; c < 16 * ntc; c += 4) {
-          int gt = cu + G * (tile_first + (c >> 4));
-          best = top_merge2(best, Top{tile1<NW, REG>(io.lds0, (unsigned)(row * LDT + c) * 4u), 16 * gt + (c & 15), -INFINITY});
+        for (int c8 = j; c8 < 2 * ntc; c8 += 4) {  // eight columns at a time
+          float v[8];
+          tile8<NW, REG>(io.lds0, (unsigned)(row * LDT + 8 * c8) * 4u, v);
+          const int col0 = 16 * (cu + G * (tile_first + (c8 >> 1))) + 8 * (c8 & 1);
+#pragma unroll
+          for (int k = 0; k < 8; ++k) best = top_merge2(best, Top{v[k], col0 + k, -INFINITY});
         }
 #pragma unroll
       for (int o = 1; o < 4; o <<= 1) {
