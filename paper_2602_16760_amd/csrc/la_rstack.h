@@ -9,7 +9,8 @@
 //   * One workgroup of 8 waves per CU stays resident.  Waves 0..NW-1 are MFMA WAVES.  Each owns a
 //     private, contiguous stream of weight fragments (every NW-th k-tile of the CU's column
 //     tiles, in the order it will use them, across GEMMs and layers) and keeps the next D = 32
-//     fragments of it in flight or landed in its own registers (buffer_load_dwordx4 ... nt, one
+//     fragments of it (24 and 16 for blocks of 48 and 64 rows, whose accumulators need the
+//     registers) in flight or landed in its own registers (buffer_load_dwordx4 ... nt, one
 //     s_waitcnt vmcnt(D-1) per use: the wave touches memory for nothing else, so the counter
 //     counts weight fragments only).  A fragment is re-requested the moment the matrix unit has
 //     read it, whatever GEMM the next fragment belongs to: the streams run ahead across every
@@ -245,10 +246,11 @@ struct BodyCursor {
 };
 
 // ---- the MFMA waves' schedule -----------------------------------------------------------------------
-// What an MFMA wave does is the same in every layer of a launch.  One thread per MFMA wave
-// writes it down once, at the start of the kernel, as a table of bodies in LDS (offsets relative
-// to the layer); the wave's own loop then only reads the table, so that it holds little state
-// besides its ring and accumulators and never touches scratch memory.
+// What an MFMA wave does is the same in every layer of a launch, and in every launch of a model
+// with the same row-tile count.  It is written down once per model (schedule_tables_kernel, one
+// thread per MFMA wave of every workgroup) as a table of bodies (offsets relative to the layer)
+// that every launch copies into LDS; the wave's own loop then only reads the table, so that it
+// holds little state besides its ring and accumulators and never touches scratch memory.
 struct BodyEnt {
   unsigned mask;    // real slots of the body
   unsigned frag;    // fragment index, relative to the layer's segment, of slot 0
