@@ -378,6 +378,20 @@ def test_error_paths():
         eng.close()
 
 
+def test_a_shape_whose_schedule_does_not_fit_is_refused(monkeypatch):
+    """The MFMA waves of the persistent kernel follow a table with a fixed number of entries per
+    layer.  With the 7B shape on four workgroups a workgroup has 448 gate/up column tiles (56 passes
+    of eight bodies each): the model must be refused when it is created, with LA_EINVAL and a message
+    that names the table, before anything is allocated for the weights; the same shape on all
+    workgroups is what the benchmarks run."""
+    from paper_2602_16760_amd import binding as B
+    shape = synth.SHAPES["mistral7b"].with_layers(1)
+    monkeypatch.setenv("LA_WGS", "4")
+    with pytest.raises(B.LaError) as e:
+        B.la_init_model(shape, None, None, None)
+    assert e.value.code == -1 and "schedule" in str(e.value)
+
+
 def test_barrier_timeout_is_reported_and_the_model_recovers():
     """The error path of the persistent kernel, forced from the host: with the grid barrier's
     patience set to one poll the workgroups that arrive first give up, every wave of the kernel
