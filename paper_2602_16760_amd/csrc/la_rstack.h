@@ -68,7 +68,7 @@ constexpr int M_RS = 0;        // [64] row factors of the norm
 constexpr int M_CTL = 256;     // control words
 constexpr int M_CONST = 512;   // LaunchConst
 constexpr int M_EPI = 640;     // EpiPtrs of the running pass
-constexpr int M_SINK = 768;    // cache-warming loads land here; never read
+constexpr int M_SINK = 768;    // (spare)
 constexpr int M_GAIN = 1024;   // norm gains of this workgroup's x columns
 constexpr int M_X = 1280;      // this workgroup's columns of x: [column tile][row][16] floats
 constexpr int X_BYTES = 4096;
@@ -1162,31 +1162,6 @@ __device__ __forceinline__ void r_gain_stage(const float *gain, const Io &io, in
   __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc_of(gain), (LDS_AS void *)(uintptr_t)(io.misc + M_GAIN), 4, vo, 0, 0, 0);
 }
 
-// Requests the cache lines of the committed K, V rows of a unit's kv head (see la_stack.h's kv_touch).
-template <int NIO>
-__device__ __forceinline__ void r_kv_touch(const uint16_t *Kc, const uint16_t *Vc, int u, int n_rt, int Hkv, int dh, int L, const Io &io) {
-  const int rt = u / Hkv, kvh = u - rt * Hkv;
-  const int kb_split = L >> 5;
-  const int k_lines_row = dh >> 6, v_lines_blk = dh >> 1;
-  if (k_lines_row == 0) return;
-  const int nlk = kb_split * 32 * k_lines_row, nl = nlk + kb_split * v_lines_blk;
-  __amdgpu_buffer_rsrc_t rk = rsrc_of(Kc), rv = rsrc_of(Vc);
-  LDS_AS void *sink = (LDS_AS void *)(uintptr_t)(io.misc + M_SINK);
-  for (int t0 = (rt * NIO + io.v) * 64; t0 < nl; t0 += n_rt * NIO * 64) {
-    const int t = t0 + io.lane;
-    unsigned ko = OOB, vo = OOB;
-    if (t < nlk) {
-      const int row = t / k_lines_row, part = t - row * k_lines_row;
-      ko = (unsigned)((((size_t)row * Hkv + kvh) * dh) * 2 + part * 128);
-    } else if (t < nl) {
-      const int j = t - nlk, kb = j / v_lines_blk, l = j - kb * v_lines_blk;
-      vo = (unsigned)((((size_t)kb * Hkv + kvh) * dh * 32) * 2 + l * 128);
-    }
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rk, sink, 4, ko, 0, 0, 0);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, sink, 4, vo, 0, 0, 0);
-  }
-}
-
 // ---- masked-block GQA attention on the IO waves -----------------------------------------------------
 // Same unit, same products and the same running softmax as la_stack.h's attention_phase; the NIO
 // waves of a unit's workgroup split the 32-key blocks, and wave 0 merges the others' partial
@@ -1216,7 +1191,8 @@ __device__ __forceinline__ bool r_attention(const StackArgs &a, Io &io, const ui
   for (int su = su0; su < n_units * S; su += gridDim.x) {
     const int u = su % n_units, ks = su / n_units;
     // unit u = kvh + Hkv * rt sits on workgroup att_first + u: with 8 kv heads (and the first unit on a multiple of 8)
-    // all units of a kv head run on one XCD and share its K, V lines in that XCD's L2 (r_kv_touch warms exactly those)
+    // all units of a kv head run on one XCD and share its K, V lines in that XCD's L2 (requesting those lines ahead, during
+    // the QKV phase, as the earlier kernel does, was measured here and costs 0.5 - 2.4 %: it is not done)
     const int rt = u / a.Hkv, kvh = u - rt * a.Hkv;
     const int b = (rt % MT) * 16 + c16;
     io_mark(io, 10);  // (timeline of a unit: entry, late blocks done, early blocks done, merged, stored)
@@ -1589,8 +1565,6 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
         ++pseq;
         io_mark(io, 11);
       }
-      if (gemm == 0)
-        for (int u = att_u0; u < n_units; u += gridDim.x) r_kv_touch<NIO>(Kc, Vc, u, n_rt, a.Hkv, a.dh, L, io);  // (the first slice's workgroups)
     }
   }
   io_mark(io, 2);
