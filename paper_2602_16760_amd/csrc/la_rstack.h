@@ -855,6 +855,7 @@ struct Epi {
   uint16_t *act_a;
   Top *un_part;
   int part;
+  bool keep_x;  // residual epilogue: x may stay in LDS alone (a later epilogue of the launch writes it to memory)
 };
 
 // The rotation factors of a thread's item of the QKV epilogue (16 floats: cos, sin of eight pairs), requested before
@@ -1002,8 +1003,12 @@ __device__ __forceinline__ void pass_epilogue(const StackArgs &a, const Io &io, 
         xs[0] = x0;
         xs[1] = x1;
       }
-      xp[0] = x0;
-      xp[1] = x1;
+      // (x goes to memory when the launch ends, or when it is not kept in LDS: these 32-byte pieces of rows 4 d bytes
+      // apart are partial cache lines, and storing them in every residual epilogue cost 1.5 us per phase)
+      if (!(x_lds && q.keep_x)) {
+        xp[0] = x0;
+        xp[1] = x1;
+      }
       float sq = 0.f;
 #pragma unroll
       for (int i = 0; i < 4; ++i) sq += x0[i] * x0[i] + x1[i] * x1[i];
@@ -1541,7 +1546,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
           A = xa0; rsq_in = rsq0; q.mode = MODE_QKV; q.Kc = Kc; q.Vc = Vc;
           break;
         case 1:
-          A = attn_l; q.mode = MODE_RESID; q.gain = a.gains[layer].g_mlp; q.xa_out = xa1; q.rsq_out = rsq1;
+          A = attn_l; q.mode = MODE_RESID; q.gain = a.gains[layer].g_mlp; q.xa_out = xa1; q.rsq_out = rsq1; q.keep_x = true;
           break;
         case 2:
           A = xa1; rsq_in = rsq1; q.mode = MODE_GATEUP; q.act_a = act_l;
@@ -1549,7 +1554,7 @@ __device__ __forceinline__ void io_wave_main(const StackArgs &a, unsigned lds0, 
         default:
           A = act_l; q.mode = MODE_RESID;
           q.gain = layer + 1 < a.le ? a.gains[layer + 1].g_attn : nullptr;
-          q.xa_out = xa0 + 2 * a.xa_stride; q.rsq_out = rsq0 + 2 * a.rsq_stride;
+          q.xa_out = xa0 + 2 * a.xa_stride; q.rsq_out = rsq0 + 2 * a.rsq_stride; q.keep_x = layer + 1 < a.le;
           break;
       }
       if (q.mode == MODE_RESID && x_lds) r_gain_stage(q.gain, io, nt_x);
